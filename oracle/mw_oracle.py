@@ -1,0 +1,350 @@
+"""Plain CPU statement of what MultiWorld's worlds compute (numpy only).
+
+TEST INFRASTRUCTURE ONLY -- see the package docstring.  Every function cites
+the passage of the paper (arXiv 2407.08980) it restates.
+
+The paper's data plane has exact definitions, so the oracle is the definition
+written out, processed strictly in program (trace) order with no concurrency:
+
+* a *world* is a fixed set of workers forming one fault domain; a worker may
+  be in many worlds; a worker's failure breaks exactly the worlds that contain
+  it (Sec. 3.1 "Overview", Fig. 2).
+* collective operations are addressed by world (Sec. 1, contributions) and
+  are non-blocking: an operation whose peers have not arrived stays pending
+  and must not hold up any other world (Sec. 3.2 "Non-blocking CCL
+  operations").
+* send/recv, broadcast and all-reduce are the four of the communicator's
+  eight operations covered here (Sec. 3.3 "World Communicator").
+* when a world is broken the manager fences it off, aborts its pending
+  operations and raises to the application; later access is refused
+  (Sec. 3.3 "World Manager"); everything that completed before the failure
+  stays delivered (Sec. 4.1, Fig. 4: the ten tensors sent before the kill all
+  arrive).
+
+Where the paper is silent the readings are:
+
+* matching of point-to-point operations: per (world, src, dst) first-in
+  first-out, no tags -- the k-th send pairs with the k-th recv;
+* a send completes only when its recv has been posted (rendezvous);
+* collectives: the k-th collective a rank posts in a world belongs to that
+  world's k-th collective, which executes when every rank has posted it;
+* all-reduce is in place and leaves the same tensor on every rank;
+* sides that disagree on count, dtype, kind or root yield MISMATCH and move
+  no data.
+
+Pinned by tests/test_oracle_pins.py (identity, brute force, exact-arithmetic
+special cases, the paper's Fig. 2 and Fig. 4 scenarios).  Throughput figures
+of the paper are for other hardware and are not part of the oracle.
+"""
+
+from __future__ import annotations
+
+from collections import deque
+
+import numpy as np
+
+# dtypes ---------------------------------------------------------------------
+F32 = "f32"
+BF16 = "bf16"
+_ITEMSIZE = {F32: 4, BF16: 2}
+
+# per-handle results and per-world states --------------------------------------
+DONE = "done"
+PENDING = "pending"
+BROKEN = "broken"
+MISMATCH = "mismatch"
+ALIVE = "alive"
+
+
+class OracleError(Exception):
+    """Argument errors; .code is one of EINVAL, ENOWORLD, EEXIST."""
+
+    def __init__(self, code, msg=""):
+        super().__init__(f"{code}: {msg}")
+        self.code = code
+
+
+# ---------------------------------------------------------------------------
+# bf16 <-> f32 (bf16 = the upper 16 bits of an IEEE-754 binary32)
+# ---------------------------------------------------------------------------
+def bf16_bits_to_f32(bits):
+    """Widen bf16 bit patterns (uint16) to float32: exact, low 16 bits zero."""
+    bits = np.asarray(bits, dtype=np.uint16)
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def f32_to_bf16_bits(x):
+    """Round float32 to bf16, nearest with ties to even; NaN stays a quiet NaN."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    r = ((u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)).astype(np.uint16)
+    nan = np.isnan(x)
+    if nan.any():
+        r = np.where(nan, ((u >> np.uint64(16)) | np.uint64(0x0040)).astype(np.uint16), r)
+    return r
+
+
+def _as_bytes(buf):
+    a = np.asarray(buf)
+    if a.dtype != np.uint8 or a.ndim != 1:
+        raise OracleError("EINVAL", "buffers are 1-D uint8 views")
+    return a
+
+
+def _values_f64(raw, count, dtype):
+    """Read `count` elements of `dtype` from a byte buffer as float64."""
+    n = count * _ITEMSIZE[dtype]
+    if dtype == F32:
+        return raw[:n].view(np.float32).astype(np.float64)
+    return bf16_bits_to_f32(raw[:n].view(np.uint16)).astype(np.float64)
+
+
+# ---------------------------------------------------------------------------
+# what each operation computes (Sec. 3.3, "World Communicator")
+# ---------------------------------------------------------------------------
+def copy_result(src_bytes):
+    """send/recv: the receiver's tensor is the sender's tensor, byte for byte."""
+    return np.array(_as_bytes(src_bytes), copy=True)
+
+
+def broadcast_result(bufs, root):
+    """broadcast: every rank ends with the root's tensor; the root's is unchanged."""
+    rootb = _as_bytes(bufs[root])
+    return [np.array(rootb, copy=True) for _ in bufs]
+
+
+def allreduce_sum_f64(bufs, count, dtype):
+    """all-reduce (sum): element-wise sum over the ranks, taken in float64.
+
+    Returns (s, sabs): s[i] = sum_r x_r[i] and sabs[i] = sum_r |x_r[i]|, the
+    scale of the forward error bound of any summation order.
+    """
+    s = np.zeros(count, dtype=np.float64)
+    sabs = np.zeros(count, dtype=np.float64)
+    for b in bufs:
+        v = _values_f64(_as_bytes(b), count, dtype)
+        s += v
+        sabs += np.abs(v)
+    return s, sabs
+
+
+def allreduce_sum_ordered(bufs, count, dtype):
+    """all-reduce (sum) in float32, ranks added in ascending order
+    ((x0 + x1) + x2) + ..., bf16 results rounded once, to nearest even.
+
+    This is the arithmetic a float32 machine performs when it fixes the order;
+    it is the bit-exact companion of the float64 definition above.  Returns the
+    result as bytes of `dtype`.
+    """
+    acc = None
+    for b in bufs:
+        raw = _as_bytes(b)[: count * _ITEMSIZE[dtype]]
+        v = raw.view(np.float32) if dtype == F32 else bf16_bits_to_f32(raw.view(np.uint16))
+        acc = v.astype(np.float32) if acc is None else (acc + v).astype(np.float32)
+    if dtype == F32:
+        return acc.view(np.uint8).copy()
+    return f32_to_bf16_bits(acc).view(np.uint8).copy()
+
+
+def allreduce_within_tolerance(y_bytes, s, sabs, count, dtype, tol=None):
+    """Check a device result y against the float64 sum s.
+
+    Bar: |y - s| <= tol * max(sum_r |x_r|, 2**-126) per element with
+    tol = 1e-6 for float32 and 1e-2 for bf16.  Returns (ok, worst) where
+    worst = max |y - s| / max(sabs, 2**-126).
+    """
+    if tol is None:
+        tol = 1e-6 if dtype == F32 else 1e-2
+    y = _values_f64(_as_bytes(y_bytes), count, dtype)
+    if count == 0:
+        return True, 0.0
+    if not np.all(np.isfinite(y)):
+        return False, float("inf")
+    ratio = np.abs(y - s) / np.maximum(sabs, 2.0 ** -126)
+    worst = float(ratio.max())
+    return worst <= tol, worst
+
+
+def broken_worlds_of_worker(worlds, worker):
+    """Fault domain rule (Sec. 3.1): a failed worker breaks the worlds that
+    contain it and no other.  `worlds` maps world id -> iterable of workers."""
+    return {w for w, members in worlds.items() if worker in members}
+
+
+# ---------------------------------------------------------------------------
+# the state machine
+# ---------------------------------------------------------------------------
+class _World:
+    __slots__ = ("members", "state", "sends", "recvs", "coll", "coll_next", "coll_base")
+
+    def __init__(self, members):
+        self.members = tuple(members)
+        self.state = ALIVE
+        self.sends = {}  # (src, dst) -> deque of unmatched sends
+        self.recvs = {}  # (src, dst) -> deque of unmatched recvs
+        self.coll = deque()  # partially posted collectives, oldest first
+        self.coll_base = 0  # sequence number of self.coll[0]
+        self.coll_next = [0] * len(self.members)  # per rank: next collective seq
+
+
+class WorldOracle:
+    """Processes a trace of world operations in program order."""
+
+    def __init__(self, n_workers):
+        if n_workers <= 0:
+            raise OracleError("EINVAL", "n_workers")
+        self.n_workers = n_workers
+        self.worlds = {}
+        self.result = []  # handle -> DONE / PENDING / BROKEN / MISMATCH
+        self.reduce_ref = {}  # handle -> (s, sabs) of a DONE all-reduce
+
+    # -- world manager (Sec. 3.3 "World Manager": initialize_world) ---------
+    def create(self, world, members):
+        members = tuple(int(m) for m in members)
+        if world in self.worlds:
+            raise OracleError("EEXIST", f"world {world}")
+        if len(members) < 1 or len(set(members)) != len(members):
+            raise OracleError("EINVAL", "members must be distinct")
+        if any(m < 0 or m >= self.n_workers for m in members):
+            raise OracleError("EINVAL", "worker id out of range")
+        self.worlds[world] = _World(members)
+
+    def world_state(self, world):
+        return self._world(world).state
+
+    def status(self, h):
+        return self.result[h]
+
+    # -- helpers ----------------------------------------------------------------
+    def _world(self, world):
+        w = self.worlds.get(world)
+        if w is None:
+            raise OracleError("ENOWORLD", f"world {world}")
+        return w
+
+    def _new(self, st):
+        self.result.append(st)
+        return len(self.result) - 1
+
+    @staticmethod
+    def _check_buf(buf, count, dtype):
+        if dtype not in _ITEMSIZE or count < 0:
+            raise OracleError("EINVAL", "count/dtype")
+        if buf is not None and _as_bytes(buf).size < count * _ITEMSIZE[dtype]:
+            raise OracleError("EINVAL", "buffer shorter than count elements")
+
+    # -- send / recv (Sec. 3.3; arrival order is arbitrary, Sec. 3.2) -------
+    def _post_p2p(self, is_send, world, src, dst, buf, count, dtype):
+        w = self._world(world)
+        n = len(w.members)
+        if not (0 <= src < n and 0 <= dst < n) or src == dst:
+            raise OracleError("EINVAL", "ranks")
+        self._check_buf(buf, count, dtype)
+        if w.state == BROKEN:  # access to a broken world is refused
+            return self._new(BROKEN)
+        h = self._new(PENDING)
+        mine, theirs = (w.sends, w.recvs) if is_send else (w.recvs, w.sends)
+        q = theirs.get((src, dst))
+        if q:
+            oh, obuf, ocount, odtype = q.popleft()
+            sbuf, rbuf = (buf, obuf) if is_send else (obuf, buf)
+            if (ocount, odtype) != (count, dtype):
+                self.result[h] = self.result[oh] = MISMATCH
+            else:
+                if sbuf is not None and rbuf is not None:
+                    nb = count * _ITEMSIZE[dtype]
+                    _as_bytes(rbuf)[:nb] = copy_result(_as_bytes(sbuf)[:nb])
+                self.result[h] = self.result[oh] = DONE
+        else:
+            mine.setdefault((src, dst), deque()).append((h, buf, count, dtype))
+        return h
+
+    def post_send(self, world, src, dst, buf, count, dtype):
+        return self._post_p2p(True, world, src, dst, buf, count, dtype)
+
+    def post_recv(self, world, src, dst, buf, count, dtype):
+        return self._post_p2p(False, world, src, dst, buf, count, dtype)
+
+    # -- collectives (Sec. 3.3: broadcast, all-reduce) ------------------------
+    def _post_coll(self, kind, world, rank, root, buf, count, dtype):
+        w = self._world(world)
+        n = len(w.members)
+        if not (0 <= rank < n) or (kind == "bcast" and not (0 <= root < n)):
+            raise OracleError("EINVAL", "ranks")
+        self._check_buf(buf, count, dtype)
+        if w.state == BROKEN:
+            return self._new(BROKEN)
+        h = self._new(PENDING)
+        seq = w.coll_next[rank]
+        w.coll_next[rank] += 1
+        idx = seq - w.coll_base
+        while len(w.coll) <= idx:
+            w.coll.append({})
+        slot = w.coll[idx]
+        slot[rank] = (h, kind, root, buf, count, dtype)
+        # collectives of a world execute in sequence order once all ranks posted
+        while w.coll and len(w.coll[0]) == n:
+            self._run_coll(w.coll.popleft(), n)
+            w.coll_base += 1
+        return h
+
+    def _run_coll(self, slot, n):
+        posts = [slot[r] for r in range(n)]
+        hs = [p[0] for p in posts]
+        sig = {(p[1], p[2], p[4], p[5]) for p in posts}
+        if len(sig) != 1:
+            for h in hs:
+                self.result[h] = MISMATCH
+            return
+        kind, root, count, dtype = next(iter(sig))
+        bufs = [p[3] for p in posts]
+        nb = count * _ITEMSIZE[dtype]
+        if all(b is not None for b in bufs):
+            raws = [_as_bytes(b)[:nb] for b in bufs]
+            if kind == "bcast":
+                out = broadcast_result(raws, root)
+                for r in range(n):
+                    if r != root:
+                        raws[r][:] = out[r]
+            else:
+                s, sabs = allreduce_sum_f64(raws, count, dtype)
+                for h in hs:
+                    self.reduce_ref[h] = (s, sabs)
+                if dtype == F32:
+                    outb = s.astype(np.float32).view(np.uint8)
+                else:
+                    outb = f32_to_bf16_bits(s.astype(np.float32)).view(np.uint8)
+                for r in range(n):
+                    raws[r][:] = outb
+        for h in hs:
+            self.result[h] = DONE
+
+    def post_broadcast(self, world, rank, root, buf, count, dtype):
+        return self._post_coll("bcast", world, rank, root, buf, count, dtype)
+
+    def post_allreduce(self, world, rank, buf, count, dtype):
+        return self._post_coll("allreduce", world, rank, 0, buf, count, dtype)
+
+    # -- faults (Sec. 3.1 fault domains; Sec. 3.3 manager aborts pending ops) ---
+    def abort_world(self, world):
+        w = self._world(world)
+        if w.state == BROKEN:
+            return
+        w.state = BROKEN
+        for table in (w.sends, w.recvs):
+            for q in table.values():
+                for item in q:
+                    self.result[item[0]] = BROKEN
+            table.clear()
+        for slot in w.coll:
+            for post in slot.values():
+                self.result[post[0]] = BROKEN
+        w.coll.clear()
+
+    def abort_worker(self, worker):
+        if not (0 <= worker < self.n_workers):
+            raise OracleError("EINVAL", "worker id out of range")
+        members = {wid: w.members for wid, w in self.worlds.items()}
+        for wid in sorted(broken_worlds_of_worker(members, worker)):
+            self.abort_world(wid)
