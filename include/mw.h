@@ -1,0 +1,183 @@
+/*
+ * mw.h -- C ABI of the multi-world tensor data plane for one AMD MI355X.
+ *
+ * Model (arXiv 2407.08980, "Enabling Elastic Model Serving with MultiWorld"):
+ * a *world* is a process group with a fixed set of ranks and is one fault
+ * domain; a worker may belong to many worlds at once; collective operations
+ * name the world they run in; they never block, their status is polled; when
+ * a worker fails only the worlds that contain it break, and every other world
+ * keeps working (Sec. 3.1, 3.2, 3.3).
+ *
+ * Here the workers are *logical*: they all live in the calling process and
+ * share one GPU, so a transfer is a device-local read and write.  Each rank
+ * posts its own side of an operation (mw_send by the sender, mw_recv by the
+ * receiver, one mw_broadcast / mw_allreduce_sum call per rank), because the
+ * ranks stand for independent processes and "the other side never arrives"
+ * must be expressible (Sec. 3.2).  An operation runs when its last side has
+ * been posted; all data movement is done by GPU kernels of this library.
+ *
+ * Conventions for every function
+ *   - returns MW_OK (0) or a negative mw_err; mw_poll / mw_world_state return a
+ *     non-negative state or a negative mw_err.  Nothing throws, aborts or
+ *     blocks on the device (mw_shutdown and the mw_debug_* calls excepted).
+ *   - `buf` arguments are DEVICE pointers to caller-owned memory of the GPU
+ *     passed to mw_init.  The library never frees or reallocates them.  Any
+ *     alignment and any element count are accepted (16-byte aligned buffers
+ *     take the fast path).
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     The operation is ordered after all work enqueued on that stream before
+ *     the library launches it (at the latest: everything enqueued before the
+ *     post).  MW_STREAM_NONE states that the buffer is already final and no
+ *     ordering is needed.
+ *   - From the post until mw_poll returns a terminal state the sender's buffer
+ *     must not be written and the receiver's buffer must not be read or
+ *     written by the caller.  After MW_DONE the data is visible to work
+ *     enqueued afterwards on any stream and to host copies.
+ *   - All calls are serialised by one internal lock; they may come from any
+ *     host thread.
+ */
+#ifndef MW_H_
+#define MW_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* mw_poll / mw_world_state results */
+enum { MW_DONE = 0, MW_PENDING = 1, MW_BROKEN = 2, MW_ALIVE = 0 };
+
+typedef enum {
+  MW_OK = 0,
+  MW_EINVAL = -1,     /* bad argument (rank out of range, src == dst, NULL buffer with count > 0, ...) */
+  MW_ENOWORLD = -2,   /* no world with this id */
+  MW_EBROKEN = -3,    /* post refused: the world is broken (Sec. 3.3, World Manager) */
+  MW_EEXIST = -4,     /* world id already used (ids are never reused, recovery makes NEW worlds, Sec. 3.1) */
+  MW_EMISMATCH = -5,  /* the sides of an operation disagree on count, dtype, kind or root */
+  MW_ENOMEM = -6,     /* a library table is full (worlds, handles, ring arena) */
+  MW_EBADHANDLE = -7, /* handle never issued, or its slot has been recycled */
+  MW_EHIP = -8,       /* a HIP call failed; mw_last_hip_error() has the code */
+  MW_ENOTINIT = -9    /* mw_init has not been called (or failed) */
+} mw_err;
+
+typedef enum { MW_F32 = 0, MW_BF16 = 1 } mw_dtype;
+
+typedef uint64_t mw_handle; /* low 32 bits: table slot, high 32 bits: generation; 0 is never issued */
+
+#define MW_STREAM_NONE ((void*)(intptr_t)-1)
+#define MW_MAX_RANKS 64     /* ranks per world (point-to-point) */
+#define MW_MAX_COLL_RANKS 8 /* ranks per world for broadcast / all-reduce */
+
+/* ---- context --------------------------------------------------------------------------- */
+
+/* Create the library context on HIP device `hip_device` for logical workers 0..n_workers-1.
+ * Allocates (once) the ring arena in HBM, the device and host-pinned completion arrays and an
+ * internal stream.  One context per process.  MW_EINVAL if already initialised or n_workers<1,
+ * MW_EHIP if the device cannot be used. */
+int mw_init(int hip_device, int n_workers);
+
+/* Wait for in-flight operations, free everything.  Blocks.  Handles become invalid. */
+int mw_shutdown(void);
+
+/* ---- world manager (Sec. 3.3 "World Manager": initialize_world / remove_world) ---------- */
+
+/* Create world `world_id` whose rank r is worker worker_ids[r] (host array, read during the
+ * call).  Gives the world its own mailbox ring (a slice of the HBM arena).  Never disturbs
+ * traffic of existing worlds: no device synchronisation, no allocation (online instantiation,
+ * Sec. 3.1).  1 <= n_ranks <= MW_MAX_RANKS, workers distinct and < n_workers. */
+int mw_world_create(int world_id, const int* worker_ids, int n_ranks);
+
+/* Break a world: it is fenced off (later posts return MW_EBROKEN), every operation of it that is
+ * still waiting for a peer becomes MW_BROKEN, operations that already had all their sides are
+ * completed normally (what was sent before a failure is delivered, Sec. 4.1 / Fig. 4).  The
+ * world's ring is released once its in-flight operations have retired.  No other world is
+ * touched, stalled or synchronised.  Idempotent. */
+int mw_world_abort(int world_id);
+
+/* A worker failed: abort every world that contains it, and no other (Sec. 3.1, Fig. 2). */
+int mw_worker_abort(int worker_id);
+
+/* MW_ALIVE, MW_BROKEN or MW_ENOWORLD. */
+int mw_world_state(int world_id);
+
+/* ---- world communicator (Sec. 3.3 "World Communicator"), all non-blocking (Sec. 3.2) ----- */
+
+/* Point-to-point.  Matching is first-in first-out per (world, src_rank, dst_rank), no tags: the
+ * k-th send pairs with the k-th recv.  A send completes only when its recv has been posted and the
+ * bytes are in the receiver's buffer.  `count` elements of `dtype`; the transfer is byte-exact.
+ * On success *out is a handle for mw_poll.  Sides that disagree on count or dtype both poll as
+ * MW_EMISMATCH and nothing is moved. */
+int mw_send(int world_id, int src_rank, int dst_rank, const void* buf, size_t count, mw_dtype dtype,
+            void* hip_stream, mw_handle* out);
+int mw_recv(int world_id, int src_rank, int dst_rank, void* buf, size_t count, mw_dtype dtype,
+            void* hip_stream, mw_handle* out);
+
+/* Broadcast, posted once by every rank of the world with its own buffer: afterwards every rank's
+ * buffer holds root_rank's bytes; the root's buffer is only read.  The k-th collective a rank posts
+ * in a world belongs to that world's k-th collective; it runs when all ranks have posted it.
+ * Worlds of at most MW_MAX_COLL_RANKS ranks. */
+int mw_broadcast(int world_id, int rank, int root_rank, void* buf, size_t count, mw_dtype dtype,
+                 void* hip_stream, mw_handle* out);
+
+/* Sum all-reduce, in place, posted once by every rank: afterwards every rank's buffer holds the
+ * element-wise sum over the ranks.  Accumulation is in fp32 in ascending rank order
+ * ((x0 + x1) + x2) + ..., so results are deterministic and bit-identical on all ranks; bf16
+ * results are rounded once, to nearest even.  Worlds of at most MW_MAX_COLL_RANKS ranks; `buf` must
+ * be aligned to the element size (MW_EINVAL otherwise). */
+int mw_allreduce_sum(int world_id, int rank, void* buf, size_t count, mw_dtype dtype, void* hip_stream,
+                     mw_handle* out);
+
+/* Status of an operation: MW_DONE, MW_PENDING, MW_BROKEN, or MW_EMISMATCH / MW_EBADHANDLE.  Never
+ * blocks and never synchronises the device: completion is read from a host-visible flag that the
+ * GPU writes when the operation's last chunk has retired (Sec. 3.2: asynchronous operations need
+ * their status polled).  Polling an operation that is complete on the host side but not yet
+ * launched launches it.  Terminal states are sticky; a handle stays valid until its table slot is
+ * reused (at least mw_handle_capacity() further posts). */
+int mw_poll(mw_handle h);
+
+/* ---- extensions ----------------------------------------------------------------------------- */
+
+/* Launch every operation whose sides have all been posted (one batched launch per kernel kind,
+ * covering operations of all worlds).  mw_poll does this on demand; calling it after a group of
+ * posts batches them into one launch. */
+int mw_flush(void);
+
+/* Number of operations that have all their sides posted and have not yet been seen complete by a
+ * poll (queued for launch or in flight).  0 means every remaining MW_PENDING handle waits for a peer. */
+int mw_pending_ops(void);
+
+/* Poll n handles at once: states[i] = mw_poll(handles[i]).  Returns the number not yet terminal. */
+int mw_poll_many(const mw_handle* handles, int n, int* states);
+
+/* Tunables, to be set between mw_init and the first post.  key: "chunk_bytes" (power of two,
+ * 4096..4194304; 0 = choose per launch), "ring_depth" (1..64 slots per world), "reduce_lds"
+ * (0/1: stage all-reduce tiles through LDS).  MW_EINVAL for unknown keys or bad values. */
+int mw_config_set(const char* key, long value);
+long mw_config_get(const char* key);
+
+int mw_handle_capacity(void);
+int mw_last_hip_error(void);
+const char* mw_strerror(int err);
+
+/* Per-kernel timing with HIP events on the library's own stream.  mw_profile_enable(1) starts
+ * bracketing every data-kernel launch with events; mw_profile_read sums the finished launches of
+ * kernel kind `kind` (0 copy, 1 broadcast, 2 all-reduce): number of launches, total milliseconds
+ * and total payload-descriptor bytes (sum of nbytes over operations).  Reading waits for the
+ * recorded events (blocks); it is for benchmarks, not for the data path. */
+int mw_profile_enable(int on);
+int mw_profile_read(int kind, uint64_t* launches, double* total_ms, uint64_t* op_bytes);
+
+/* Diagnostics (block until the library's stream is idle).
+ * mw_debug_ring_read copies world `world_id`'s ring header and slots from HBM to `out` (host):
+ * returns the number of bytes written, or a negative error; MW_EINVAL if cap is too small.
+ * mw_debug_arena_hash returns an FNV-1a hash of every ring byte NOT belonging to `except_world`
+ * (pass -1 to hash everything) so that tests can show a teardown touched nothing else. */
+long mw_debug_ring_read(int world_id, void* out, size_t cap);
+int mw_debug_arena_hash(int except_world, uint64_t* hash);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MW_H_ */

@@ -1,0 +1,229 @@
+"""ctypes binding of libmw.so: the same names as include/mw.h, argument marshalling only.
+
+Buffers are passed as integer device addresses (e.g. torch.Tensor.data_ptr()), streams as
+integer hipStream_t values (e.g. torch.cuda.Stream.cuda_stream; 0 = the null stream,
+STREAM_NONE = no ordering needed).  Calls that return a status raise MwError on a negative
+code, except mw_poll, whose negative codes are states of the operation and are returned.
+There is no fallback: if the library is missing or fails to load, the first call raises.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmw.so")
+
+# mw_poll / mw_world_state results and error codes (mirrors include/mw.h)
+MW_DONE, MW_PENDING, MW_BROKEN, MW_ALIVE = 0, 1, 2, 0
+MW_OK, MW_EINVAL, MW_ENOWORLD, MW_EBROKEN, MW_EEXIST = 0, -1, -2, -3, -4
+MW_EMISMATCH, MW_ENOMEM, MW_EBADHANDLE, MW_EHIP, MW_ENOTINIT = -5, -6, -7, -8, -9
+MW_F32, MW_BF16 = 0, 1
+DTYPES = {"f32": MW_F32, "bf16": MW_BF16}
+STREAM_NONE = -1
+KIND_COPY, KIND_BCAST, KIND_REDUCE = 0, 1, 2
+
+SYMBOLS = [
+    "mw_init", "mw_shutdown", "mw_world_create", "mw_world_abort", "mw_worker_abort", "mw_world_state",
+    "mw_send", "mw_recv", "mw_broadcast", "mw_allreduce_sum", "mw_poll", "mw_flush", "mw_pending_ops", "mw_poll_many",
+    "mw_config_set", "mw_config_get", "mw_handle_capacity", "mw_last_hip_error", "mw_strerror",
+    "mw_profile_enable", "mw_profile_read", "mw_debug_ring_read", "mw_debug_arena_hash",
+]
+
+
+class MwError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def declare(lib):
+    """Set argument and result types on a loaded library (also used for the host-check build)."""
+    vp, i, sz, u64p = C.c_void_p, C.c_int, C.c_size_t, C.POINTER(C.c_uint64)
+    lib.mw_init.argtypes = [i, i]
+    lib.mw_shutdown.argtypes = []
+    lib.mw_world_create.argtypes = [i, C.POINTER(C.c_int), i]
+    lib.mw_world_abort.argtypes = [i]
+    lib.mw_worker_abort.argtypes = [i]
+    lib.mw_world_state.argtypes = [i]
+    for f in (lib.mw_send, lib.mw_recv):
+        f.argtypes = [i, i, i, vp, sz, i, vp, u64p]
+    lib.mw_broadcast.argtypes = [i, i, i, vp, sz, i, vp, u64p]
+    lib.mw_allreduce_sum.argtypes = [i, i, vp, sz, i, vp, u64p]
+    lib.mw_poll.argtypes = [C.c_uint64]
+    lib.mw_flush.argtypes = []
+    lib.mw_pending_ops.argtypes = []
+    lib.mw_poll_many.argtypes = [u64p, i, C.POINTER(C.c_int)]
+    lib.mw_config_set.argtypes = [C.c_char_p, C.c_long]
+    lib.mw_config_get.argtypes = [C.c_char_p]
+    lib.mw_config_get.restype = C.c_long
+    lib.mw_handle_capacity.argtypes = []
+    lib.mw_last_hip_error.argtypes = []
+    lib.mw_strerror.argtypes = [i]
+    lib.mw_strerror.restype = C.c_char_p
+    lib.mw_profile_enable.argtypes = [i]
+    lib.mw_profile_read.argtypes = [i, u64p, C.POINTER(C.c_double), u64p]
+    lib.mw_debug_ring_read.argtypes = [i, vp, sz]
+    lib.mw_debug_ring_read.restype = C.c_long
+    lib.mw_debug_arena_hash.argtypes = [i, u64p]
+    return lib
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2407_08980_amd.build` "
+                               "(there is no fallback path)")
+        _lib = declare(C.CDLL(LIB_PATH))
+    return _lib
+
+
+def use_library(handle):
+    """Route the binding through an already loaded library (the CPU tests pass the host-check build)."""
+    global _lib
+    _lib = declare(handle)
+
+
+def strerror(code):
+    return lib().mw_strerror(code).decode()
+
+
+def _ck(rc, where):
+    if rc < 0:
+        raise MwError(rc, where)
+    return rc
+
+
+def _stream(s):
+    return C.c_void_p(s if s != STREAM_NONE else C.c_void_p(-1).value)
+
+
+def mw_init(hip_device, n_workers):
+    return _ck(lib().mw_init(hip_device, n_workers), "mw_init")
+
+
+def mw_shutdown():
+    return _ck(lib().mw_shutdown(), "mw_shutdown")
+
+
+def mw_world_create(world_id, worker_ids):
+    arr = (C.c_int * len(worker_ids))(*worker_ids)
+    return _ck(lib().mw_world_create(world_id, arr, len(worker_ids)), "mw_world_create")
+
+
+def mw_world_abort(world_id):
+    return _ck(lib().mw_world_abort(world_id), "mw_world_abort")
+
+
+def mw_worker_abort(worker_id):
+    return _ck(lib().mw_worker_abort(worker_id), "mw_worker_abort")
+
+
+def mw_world_state(world_id):
+    return _ck(lib().mw_world_state(world_id), "mw_world_state")
+
+
+def mw_send(world, src_rank, dst_rank, buf, count, dtype, stream=0):
+    h = C.c_uint64(0)
+    _ck(lib().mw_send(world, src_rank, dst_rank, buf, count, dtype, _stream(stream), C.byref(h)), "mw_send")
+    return h.value
+
+
+def mw_recv(world, src_rank, dst_rank, buf, count, dtype, stream=0):
+    h = C.c_uint64(0)
+    _ck(lib().mw_recv(world, src_rank, dst_rank, buf, count, dtype, _stream(stream), C.byref(h)), "mw_recv")
+    return h.value
+
+
+def mw_broadcast(world, rank, root_rank, buf, count, dtype, stream=0):
+    h = C.c_uint64(0)
+    _ck(lib().mw_broadcast(world, rank, root_rank, buf, count, dtype, _stream(stream), C.byref(h)), "mw_broadcast")
+    return h.value
+
+
+def mw_allreduce_sum(world, rank, buf, count, dtype, stream=0):
+    h = C.c_uint64(0)
+    _ck(lib().mw_allreduce_sum(world, rank, buf, count, dtype, _stream(stream), C.byref(h)), "mw_allreduce_sum")
+    return h.value
+
+
+def mw_poll(handle):
+    return lib().mw_poll(handle)
+
+
+def mw_flush():
+    return _ck(lib().mw_flush(), "mw_flush")
+
+
+def mw_pending_ops():
+    return _ck(lib().mw_pending_ops(), "mw_pending_ops")
+
+
+class PollSet:
+    """Reusable arrays for mw_poll_many over a fixed list of handles."""
+
+    def __init__(self, handles):
+        self.n = len(handles)
+        self.handles = (C.c_uint64 * self.n)(*handles)
+        self.states = (C.c_int * self.n)()
+
+    def poll(self):
+        """Number of handles still pending; self.states holds every state."""
+        return _ck(lib().mw_poll_many(self.handles, self.n, self.states), "mw_poll_many")
+
+
+def mw_poll_many(handles):
+    ps = PollSet(handles)
+    ps.poll()
+    return list(ps.states)
+
+
+def mw_config_set(key, value):
+    return _ck(lib().mw_config_set(key.encode(), value), f"mw_config_set({key})")
+
+
+def mw_config_get(key):
+    return lib().mw_config_get(key.encode())
+
+
+def mw_handle_capacity():
+    return lib().mw_handle_capacity()
+
+
+def mw_last_hip_error():
+    return lib().mw_last_hip_error()
+
+
+def mw_strerror(code):
+    return strerror(code)
+
+
+def mw_profile_enable(on):
+    return _ck(lib().mw_profile_enable(1 if on else 0), "mw_profile_enable")
+
+
+def mw_profile_read(kind):
+    """(launches, total_ms, op_bytes) of the finished launches of one kernel kind since the last read."""
+    n, ms, b = C.c_uint64(0), C.c_double(0), C.c_uint64(0)
+    _ck(lib().mw_profile_read(kind, C.byref(n), C.byref(ms), C.byref(b)), "mw_profile_read")
+    return n.value, ms.value, b.value
+
+
+def mw_debug_ring_read(world_id):
+    """Bytes of a world's ring header and slots as they are in HBM."""
+    cap = 256 + 64 * 256
+    buf = (C.c_ubyte * cap)()
+    n = lib().mw_debug_ring_read(world_id, buf, cap)
+    _ck(n, "mw_debug_ring_read")
+    return bytes(buf[:n])
+
+
+def mw_debug_arena_hash(except_world=-1):
+    h = C.c_uint64(0)
+    _ck(lib().mw_debug_arena_hash(except_world, C.byref(h)), "mw_debug_arena_hash")
+    return h.value

@@ -1,0 +1,718 @@
+// Device backend for gfx950 (MI355X): the kernels of the multi-world data plane
+// and their launch logic.
+//
+//   mw_k_copy    batched point-to-point copy: one launch moves the matched
+//                send/recv pairs of many worlds (the communicator's send/recv,
+//                arXiv 2407.08980 Sec. 3.3)
+//   mw_k_bcast   broadcast fan-out: the root's chunk is read once and written
+//                to every other rank's buffer (Sec. 3.3)
+//   mw_k_reduce  sum all-reduce among a world's logical ranks, in place, fp32
+//                accumulation in ascending rank order (Sec. 3.3)
+//   mw_k_mark    writes a world's ring header: alive at creation, broken with a
+//                bumped epoch at abort (Sec. 3.3 "World Manager")
+//
+// Every data kernel ends with the completion protocol: the workgroup that
+// retires the last chunk of an operation publishes the operation's generation
+// to the ring slot in HBM and to a host-pinned word, which is what the host
+// polls -- no HIP call, no device synchronisation (Sec. 3.2: asynchronous
+// operations report no status by themselves, so it is polled).
+//
+// All of this is bandwidth-bound work: 128-bit coalesced accesses with streaming
+// (non-temporal) hints, no matrix instructions.
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "../../include/mw.h"
+#include "mw_internal.hpp"
+
+namespace mw {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kCopyWG = 1024;   // threads per workgroup, copy / broadcast
+constexpr int kCopyU = 4;       // 16-byte vectors in flight per thread
+constexpr int kReduceWG = 256;
+constexpr int kReduceU = 2;
+constexpr int kCopyMax = 80;    // operations per copy launch (kernel arguments stay under 4 KiB)
+constexpr int kCollMax = 36;    // operations per broadcast / all-reduce launch
+
+struct CopyEnt {
+  uint64_t src, dst, nbytes;
+  uint32_t slot, gen;
+  uint32_t world_id, world_epoch;  // journalled only
+};
+struct CopyArgs {
+  uint32_t n;
+  uint32_t chunk_shift;
+  uint32_t first_chunk[kCopyMax + 1];  // first_chunk[i] = chunks before operation i; [n] = total
+  uint32_t pad;
+  CopyEnt e[kCopyMax];
+};
+static_assert(sizeof(CopyArgs) <= 4096, "kernel argument block");
+
+struct CollEnt {
+  uint64_t buf[kMaxBufs];
+  uint64_t nbytes;
+  uint32_t slot, gen, nbuf, dtype;
+  uint32_t world_id, world_epoch;  // journalled only
+};
+struct CollArgs {
+  uint32_t n;
+  uint32_t chunk_shift;
+  uint32_t first_chunk[kCollMax + 1];
+  uint32_t pad;
+  CollEnt e[kCollMax];
+};
+static_assert(sizeof(CollArgs) <= 4096, "kernel argument block");
+
+// ------------------------------------------------------------------------------------------------
+// device helpers
+// ------------------------------------------------------------------------------------------------
+
+// Index of the operation that owns chunk c: the largest i with first_chunk[i] <= c.
+__device__ __forceinline__ int find_op(const uint32_t* first_chunk, int n, uint32_t c) {
+  int lo = 0, hi = n;
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (first_chunk[mid] <= c) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// Completion protocol.  Every thread makes its stores visible device-wide, the workgroup
+// meets, then one thread counts the chunk in.  The workgroup that brings the count to
+// nchunks re-arms the counter and publishes the generation: first in the ring slot (HBM),
+// then, with system-scope release, in the host-pinned word the host polls.
+__device__ __forceinline__ void retire_chunk(RingSlot* slots, uint32_t* host_flags, uint32_t slot, uint32_t gen,
+                                             uint32_t nchunks) {
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    SlotSync* s = &slots[slot].s;
+    uint32_t prev = __hip_atomic_fetch_add(&s->arrived, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (prev + 1 == nchunks) {
+      __hip_atomic_store(&s->arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&s->done_gen, gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&host_flags[slot], gen, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ T ld_stream(const T* p) { return __builtin_nontemporal_load(p); }
+template <typename T>
+__device__ __forceinline__ void st_stream(T* p, T v) { __builtin_nontemporal_store(v, p); }
+
+// Copy `len` bytes from s to every d[0..nd) with accesses of type T (both sides aligned to T).
+// Unrolled so that U loads are in flight per thread before the first store.
+template <typename T, int WG, int U, int ND>
+__device__ __forceinline__ void move_units(const unsigned char* s, unsigned char* const* d, int nd, uint64_t len) {
+  const T* sp = reinterpret_cast<const T*>(s);
+  const uint64_t n = len / sizeof(T);
+  const uint64_t step = (uint64_t)WG * U;
+  const uint64_t full = n - n % step;
+  uint64_t i = threadIdx.x;
+  for (; i < full; i += step) {
+    T v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = ld_stream(sp + i + (uint64_t)u * WG);
+#pragma unroll
+    for (int k = 0; k < ND; ++k) {
+      if (k < nd) {
+        T* dp = reinterpret_cast<T*>(d[k]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) st_stream(dp + i + (uint64_t)u * WG, v[u]);
+      }
+    }
+  }
+  for (; i < n; i += WG) {
+    T v = ld_stream(sp + i);
+#pragma unroll
+    for (int k = 0; k < ND; ++k)
+      if (k < nd) st_stream(reinterpret_cast<T*>(d[k]) + i, v);
+  }
+  // bytes past the last whole unit
+  const uint64_t done = n * sizeof(T);
+  for (uint64_t b = done + threadIdx.x; b < len; b += WG) {
+    unsigned char v = s[b];
+#pragma unroll
+    for (int k = 0; k < ND; ++k)
+      if (k < nd) d[k][b] = v;
+  }
+}
+
+// Pick the widest access every pointer is aligned to.
+template <int WG, int U, int ND>
+__device__ __forceinline__ void move_any(const unsigned char* s, unsigned char* const* d, int nd, uint64_t len) {
+  uint64_t a = (uint64_t)s;
+#pragma unroll
+  for (int k = 0; k < ND; ++k)
+    if (k < nd) a |= (uint64_t)d[k];
+  a &= 15;
+  if (a == 0) move_units<u32x4, WG, U, ND>(s, d, nd, len);
+  else if ((a & 7) == 0) move_units<uint64_t, WG, U, ND>(s, d, nd, len);
+  else if ((a & 3) == 0) move_units<uint32_t, WG, U, ND>(s, d, nd, len);
+  else if ((a & 1) == 0) move_units<uint16_t, WG, U, ND>(s, d, nd, len);
+  else move_units<unsigned char, WG, U, ND>(s, d, nd, len);
+}
+
+// ------------------------------------------------------------------------------------------------
+// K1: batched multi-world copy
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kCopyWG) void mw_k_copy(const CopyArgs a, RingSlot* __restrict__ slots,
+                                                      uint32_t* __restrict__ host_flags) {
+  const uint32_t c = blockIdx.x;
+  const int op = find_op(a.first_chunk, (int)a.n, c);
+  const uint64_t src = a.e[op].src, dst = a.e[op].dst, nbytes = a.e[op].nbytes;
+  const uint32_t slot = a.e[op].slot, gen = a.e[op].gen;
+  const uint32_t ci = c - a.first_chunk[op];
+  const uint32_t nchunks = a.first_chunk[op + 1] - a.first_chunk[op];
+  const uint64_t off = (uint64_t)ci << a.chunk_shift;
+  const uint64_t chunk = 1ull << a.chunk_shift;
+  const uint64_t len = (nbytes - off < chunk) ? nbytes - off : chunk;
+  if (ci == 0 && threadIdx.x == 0) {  // journal the descriptor into the world's ring
+    SlotDesc* d = &slots[slot].d;
+    d->buf[0] = src;
+    d->buf[1] = dst;
+    d->nbytes = nbytes;
+    d->kind = kCopy;
+    d->dtype = 0;
+    d->nbuf = 2;
+    d->world_id = a.e[op].world_id;
+    d->world_epoch = a.e[op].world_epoch;
+    d->gen = gen;
+    d->nchunks = nchunks;
+    d->chunk_bytes = (uint32_t)chunk;
+  }
+  unsigned char* dp[1] = {reinterpret_cast<unsigned char*>(dst + off)};
+  move_any<kCopyWG, kCopyU, 1>(reinterpret_cast<const unsigned char*>(src + off), dp, 1, len);
+  retire_chunk(slots, host_flags, slot, gen, nchunks);
+}
+
+// ------------------------------------------------------------------------------------------------
+// K2: broadcast fan-out
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kCopyWG) void mw_k_bcast(const CollArgs a, RingSlot* __restrict__ slots,
+                                                       uint32_t* __restrict__ host_flags) {
+  const uint32_t c = blockIdx.x;
+  const int op = find_op(a.first_chunk, (int)a.n, c);
+  const uint64_t nbytes = a.e[op].nbytes;
+  const uint32_t slot = a.e[op].slot, gen = a.e[op].gen, nbuf = a.e[op].nbuf;
+  const uint32_t ci = c - a.first_chunk[op];
+  const uint32_t nchunks = a.first_chunk[op + 1] - a.first_chunk[op];
+  const uint64_t off = (uint64_t)ci << a.chunk_shift;
+  const uint64_t chunk = 1ull << a.chunk_shift;
+  const uint64_t len = (nbytes - off < chunk) ? nbytes - off : chunk;
+  unsigned char* dp[kMaxBufs - 1];
+#pragma unroll
+  for (int k = 0; k < kMaxBufs - 1; ++k)
+    dp[k] = (k + 1 < (int)nbuf) ? reinterpret_cast<unsigned char*>(a.e[op].buf[k + 1] + off) : nullptr;
+  if (ci == 0 && threadIdx.x == 0) {
+    SlotDesc* d = &slots[slot].d;
+#pragma unroll
+    for (int k = 0; k < kMaxBufs; ++k) d->buf[k] = (k < (int)nbuf) ? a.e[op].buf[k] : 0;
+    d->nbytes = nbytes;
+    d->kind = kBcast;
+    d->dtype = a.e[op].dtype;
+    d->nbuf = nbuf;
+    d->world_id = a.e[op].world_id;
+    d->world_epoch = a.e[op].world_epoch;
+    d->gen = gen;
+    d->nchunks = nchunks;
+    d->chunk_bytes = (uint32_t)chunk;
+  }
+  move_any<kCopyWG, kCopyU, kMaxBufs - 1>(reinterpret_cast<const unsigned char*>(a.e[op].buf[0] + off), dp,
+                                          (int)nbuf - 1, len);
+  retire_chunk(slots, host_flags, slot, gen, nchunks);
+}
+
+// ------------------------------------------------------------------------------------------------
+// K3: sum all-reduce among logical ranks
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// Round to nearest, ties to even; NaN stays a quiet NaN.
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// One 16-byte vector per rank: acc = ((x0 + x1) + x2) + ...
+template <bool BF16>
+struct Acc;
+template <>
+struct Acc<false> {
+  f32x4 v;
+  __device__ __forceinline__ void init(u32x4 x) { v = __builtin_bit_cast(f32x4, x); }
+  __device__ __forceinline__ void add(u32x4 x) { v = v + __builtin_bit_cast(f32x4, x); }
+  __device__ __forceinline__ u32x4 out() const { return __builtin_bit_cast(u32x4, v); }
+};
+template <>
+struct Acc<true> {
+  float v[8];
+  __device__ __forceinline__ void init(u32x4 x) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = bf16_to_f32(x[i] & 0xFFFFu);
+      v[2 * i + 1] = bf16_to_f32(x[i] >> 16);
+    }
+  }
+  __device__ __forceinline__ void add(u32x4 x) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] += bf16_to_f32(x[i] & 0xFFFFu);
+      v[2 * i + 1] += bf16_to_f32(x[i] >> 16);
+    }
+  }
+  __device__ __forceinline__ u32x4 out() const {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = f32_to_bf16(v[2 * i]) | (f32_to_bf16(v[2 * i + 1]) << 16);
+    return r;
+  }
+};
+
+// Register path: every thread holds U vectors of one rank at a time and folds them in.
+template <bool BF16, int NB>
+__device__ __forceinline__ void reduce_vectors(const uint64_t* buf, int nbuf, uint64_t off, uint64_t nvec) {
+  constexpr int U = kReduceU;
+  const uint64_t step = (uint64_t)kReduceWG * U;
+  for (uint64_t i = threadIdx.x; i < nvec; i += step) {
+    u32x4 x[NB][U];
+#pragma unroll
+    for (int r = 0; r < NB; ++r) {
+      if (r < nbuf) {
+        const u32x4* p = reinterpret_cast<const u32x4*>(buf[r] + off);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          uint64_t j = i + (uint64_t)u * kReduceWG;
+          if (j < nvec) x[r][u] = ld_stream(p + j);
+        }
+      }
+    }
+    u32x4 y[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      Acc<BF16> acc;
+      acc.init(x[0][u]);
+#pragma unroll
+      for (int r = 1; r < NB; ++r)
+        if (r < nbuf) acc.add(x[r][u]);
+      y[u] = acc.out();
+    }
+#pragma unroll
+    for (int r = 0; r < NB; ++r) {
+      if (r < nbuf) {
+        u32x4* p = reinterpret_cast<u32x4*>(buf[r] + off);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          uint64_t j = i + (uint64_t)u * kReduceWG;
+          if (j < nvec) st_stream(p + j, y[u]);
+        }
+      }
+    }
+  }
+}
+
+// LDS-staged path: the workgroup first lands one tile of every rank in LDS with wide loads,
+// then each thread sums its column across the staged rank tiles and writes all ranks.  The
+// staging decouples the (n x tile) read burst from the arithmetic and the write burst.
+template <bool BF16>
+__device__ __forceinline__ void reduce_vectors_lds(const uint64_t* buf, int nbuf, uint64_t off, uint64_t nvec,
+                                                   u32x4* tile) {
+  constexpr int U = kReduceU;
+  const uint64_t step = (uint64_t)kReduceWG * U;
+  for (uint64_t base = 0; base < nvec; base += step) {
+    for (int r = 0; r < nbuf; ++r) {
+      const u32x4* p = reinterpret_cast<const u32x4*>(buf[r] + off);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        uint64_t j = base + threadIdx.x + (uint64_t)u * kReduceWG;
+        if (j < nvec) tile[(r * U + u) * kReduceWG + threadIdx.x] = ld_stream(p + j);
+      }
+    }
+    __syncthreads();
+    u32x4 y[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      Acc<BF16> acc;
+      acc.init(tile[u * kReduceWG + threadIdx.x]);
+      for (int r = 1; r < nbuf; ++r) acc.add(tile[(r * U + u) * kReduceWG + threadIdx.x]);
+      y[u] = acc.out();
+    }
+    for (int r = 0; r < nbuf; ++r) {
+      u32x4* p = reinterpret_cast<u32x4*>(buf[r] + off);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        uint64_t j = base + threadIdx.x + (uint64_t)u * kReduceWG;
+        if (j < nvec) st_stream(p + j, y[u]);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// Element-wise path for tails and for buffers that are not 16-byte aligned.
+template <bool BF16>
+__device__ __forceinline__ void reduce_scalar(const uint64_t* buf, int nbuf, uint64_t off, uint64_t first,
+                                              uint64_t nelem) {
+  for (uint64_t i = first + threadIdx.x; i < nelem; i += kReduceWG) {
+    float acc;
+    if (BF16) {
+      acc = bf16_to_f32(reinterpret_cast<const uint16_t*>(buf[0] + off)[i]);
+      for (int r = 1; r < nbuf; ++r) acc += bf16_to_f32(reinterpret_cast<const uint16_t*>(buf[r] + off)[i]);
+      uint16_t o = (uint16_t)f32_to_bf16(acc);
+      for (int r = 0; r < nbuf; ++r) reinterpret_cast<uint16_t*>(buf[r] + off)[i] = o;
+    } else {
+      acc = reinterpret_cast<const float*>(buf[0] + off)[i];
+      for (int r = 1; r < nbuf; ++r) acc += reinterpret_cast<const float*>(buf[r] + off)[i];
+      for (int r = 0; r < nbuf; ++r) reinterpret_cast<float*>(buf[r] + off)[i] = acc;
+    }
+  }
+}
+
+template <bool LDS>
+__global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs a, RingSlot* __restrict__ slots,
+                                                          uint32_t* __restrict__ host_flags) {
+  __shared__ u32x4 tile[LDS ? kMaxBufs * kReduceU * kReduceWG : 1];
+  const uint32_t c = blockIdx.x;
+  const int op = find_op(a.first_chunk, (int)a.n, c);
+  const uint64_t nbytes = a.e[op].nbytes;
+  const uint32_t slot = a.e[op].slot, gen = a.e[op].gen, nbuf = a.e[op].nbuf, dtype = a.e[op].dtype;
+  const uint32_t ci = c - a.first_chunk[op];
+  const uint32_t nchunks = a.first_chunk[op + 1] - a.first_chunk[op];
+  const uint64_t off = (uint64_t)ci << a.chunk_shift;
+  const uint64_t chunk = 1ull << a.chunk_shift;
+  const uint64_t len = (nbytes - off < chunk) ? nbytes - off : chunk;
+  const uint64_t* buf = a.e[op].buf;  // unused entries are zero
+  uint64_t align = 0;
+#pragma unroll
+  for (int k = 0; k < kMaxBufs; ++k) align |= buf[k];
+  if (ci == 0 && threadIdx.x == 0) {
+    SlotDesc* d = &slots[slot].d;
+#pragma unroll
+    for (int k = 0; k < kMaxBufs; ++k) d->buf[k] = buf[k];
+    d->nbytes = nbytes;
+    d->kind = kReduce;
+    d->dtype = dtype;
+    d->nbuf = nbuf;
+    d->world_id = a.e[op].world_id;
+    d->world_epoch = a.e[op].world_epoch;
+    d->gen = gen;
+    d->nchunks = nchunks;
+    d->chunk_bytes = (uint32_t)chunk;
+  }
+  const bool bf16 = dtype == MW_BF16;
+  const uint64_t isz = bf16 ? 2 : 4;
+  const uint64_t nelem = len / isz;
+  uint64_t nvec = 0;
+  if ((align & 15) == 0) {
+    nvec = len >> 4;
+    if (LDS) {
+      if (bf16) reduce_vectors_lds<true>(buf, (int)nbuf, off, nvec, tile);
+      else reduce_vectors_lds<false>(buf, (int)nbuf, off, nvec, tile);
+    } else if (nbuf <= 2) {
+      if (bf16) reduce_vectors<true, 2>(buf, (int)nbuf, off, nvec);
+      else reduce_vectors<false, 2>(buf, (int)nbuf, off, nvec);
+    } else if (nbuf <= 4) {
+      if (bf16) reduce_vectors<true, 4>(buf, (int)nbuf, off, nvec);
+      else reduce_vectors<false, 4>(buf, (int)nbuf, off, nvec);
+    } else {
+      if (bf16) reduce_vectors<true, kMaxBufs>(buf, (int)nbuf, off, nvec);
+      else reduce_vectors<false, kMaxBufs>(buf, (int)nbuf, off, nvec);
+    }
+  }
+  const uint64_t first = nvec * (16 / isz);
+  if (first < nelem) {
+    if (bf16) reduce_scalar<true>(buf, (int)nbuf, off, first, nelem);
+    else reduce_scalar<false>(buf, (int)nbuf, off, first, nelem);
+  }
+  retire_chunk(slots, host_flags, slot, gen, nchunks);
+}
+
+// ------------------------------------------------------------------------------------------------
+// K5: world marker
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void mw_k_mark(RingHeader* __restrict__ dst, const RingHeader h) {
+  const uint32_t* w = reinterpret_cast<const uint32_t*>(&h);
+  reinterpret_cast<uint32_t*>(dst)[threadIdx.x] = w[threadIdx.x];
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side of the backend
+// ------------------------------------------------------------------------------------------------
+inline uint32_t floor_log2(uint64_t v) { return 63u - (uint32_t)__builtin_clzll(v | 1); }
+
+class HipDevice : public Device {
+ public:
+  int init(int hip_device, const DeviceConfig& cfg) override {
+    cfg_ = cfg;
+    dev_ = hip_device;
+    int count = 0;
+    if (chk(hipGetDeviceCount(&count)) || hip_device < 0 || hip_device >= count) return MW_EHIP;
+    if (chk(hipSetDevice(dev_))) return MW_EHIP;
+    const size_t hdr_bytes = (size_t)cfg.total_rings * sizeof(RingHeader);
+    const size_t slot_bytes = (size_t)cfg.total_slots * sizeof(RingSlot);
+    if (chk(hipMalloc(&arena_, hdr_bytes + slot_bytes))) return MW_EHIP;
+    if (chk(hipMemset(arena_, 0, hdr_bytes + slot_bytes))) return MW_EHIP;
+    headers_ = reinterpret_cast<RingHeader*>(arena_);
+    slots_ = reinterpret_cast<RingSlot*>(reinterpret_cast<char*>(arena_) + hdr_bytes);
+    if (chk(hipHostMalloc(&flags_host_, (size_t)cfg.total_slots * sizeof(uint32_t), hipHostMallocMapped | hipHostMallocCoherent)))
+      return MW_EHIP;
+    std::memset(flags_host_, 0, (size_t)cfg.total_slots * sizeof(uint32_t));
+    if (chk(hipHostGetDevicePointer(reinterpret_cast<void**>(&flags_dev_), flags_host_, 0))) return MW_EHIP;
+    if (chk(hipStreamCreateWithFlags(&data_, hipStreamNonBlocking))) return MW_EHIP;
+    if (chk(hipStreamCreateWithFlags(&ctl_, hipStreamNonBlocking))) return MW_EHIP;
+    dep_events_.resize(kDepEvents);
+    for (auto& e : dep_events_)
+      if (chk(hipEventCreateWithFlags(&e, hipEventDisableTiming))) return MW_EHIP;
+    if (chk(hipDeviceSynchronize())) return MW_EHIP;
+    ready_ = true;
+    return MW_OK;
+  }
+
+  void shutdown() override {
+    if (!ready_) return;
+    (void)hipSetDevice(dev_);
+    (void)hipStreamSynchronize(data_);
+    (void)hipStreamSynchronize(ctl_);
+    for (auto& e : dep_events_) (void)hipEventDestroy(e);
+    for (auto& r : prof_) {
+      (void)hipEventDestroy(r.start);
+      (void)hipEventDestroy(r.stop);
+    }
+    for (auto& e : prof_free_) (void)hipEventDestroy(e);
+    (void)hipStreamDestroy(data_);
+    (void)hipStreamDestroy(ctl_);
+    (void)hipFree(arena_);
+    (void)hipHostFree(flags_host_);
+    ready_ = false;
+  }
+
+  void set_config(const DeviceConfig& cfg) override {
+    cfg_.chunk_bytes = cfg.chunk_bytes;
+    cfg_.reduce_lds = cfg.reduce_lds;
+  }
+
+  int launch(const LaunchOp* ops, int n, void* const* streams, int n_streams) override {
+    if (chk(hipSetDevice(dev_))) return MW_EHIP;
+    // order after the callers' streams
+    for (int i = 0; i < n_streams; ++i) {
+      hipEvent_t ev = dep_events_[dep_cursor_];
+      dep_cursor_ = (dep_cursor_ + 1) % kDepEvents;
+      if (chk(hipEventRecord(ev, reinterpret_cast<hipStream_t>(streams[i])))) return MW_EHIP;
+      if (chk(hipStreamWaitEvent(data_, ev, 0))) return MW_EHIP;
+    }
+    // split by kind, keep order
+    int rc = MW_OK;
+    for (uint32_t kind = 0; kind < kNumKinds && rc == MW_OK; ++kind) {
+      idx_.clear();
+      for (int i = 0; i < n; ++i)
+        if (ops[i].kind == kind) idx_.push_back(i);
+      const size_t cap = kind == kCopy ? kCopyMax : kCollMax;
+      for (size_t at = 0; at < idx_.size() && rc == MW_OK; at += cap)
+        rc = launch_kind(kind, ops, idx_.data() + at, (int)std::min(cap, idx_.size() - at));
+    }
+    return rc;
+  }
+
+  int mark_world(uint32_t ring_index, const RingHeader& h) override {
+    if (chk(hipSetDevice(dev_))) return MW_EHIP;
+    hipLaunchKernelGGL(mw_k_mark, dim3(1), dim3(64), 0, ctl_, headers_ + ring_index, h);
+    return chk(hipGetLastError()) ? MW_EHIP : MW_OK;
+  }
+
+  uint32_t flag(uint32_t slot) override { return __atomic_load_n(&flags_host_[slot], __ATOMIC_ACQUIRE); }
+
+  int read_ring(uint32_t ring_index, uint32_t first_slot, uint32_t depth, void* out) override {
+    int rc = sync();
+    if (rc != MW_OK) return rc;
+    if (chk(hipMemcpy(out, headers_ + ring_index, sizeof(RingHeader), hipMemcpyDeviceToHost))) return MW_EHIP;
+    if (chk(hipMemcpy(reinterpret_cast<char*>(out) + sizeof(RingHeader), slots_ + first_slot,
+                      (size_t)depth * sizeof(RingSlot), hipMemcpyDeviceToHost)))
+      return MW_EHIP;
+    return MW_OK;
+  }
+
+  int sync() override {
+    if (chk(hipSetDevice(dev_))) return MW_EHIP;
+    if (chk(hipStreamSynchronize(data_))) return MW_EHIP;
+    if (chk(hipStreamSynchronize(ctl_))) return MW_EHIP;
+    return MW_OK;
+  }
+
+  int last_hip_error() override { return last_err_; }
+
+  int profile_enable(int on) override {
+    profiling_ = on != 0;
+    return MW_OK;
+  }
+
+  int profile_read(int kind, uint64_t* launches, double* ms, uint64_t* bytes) override {
+    if (chk(hipSetDevice(dev_))) return MW_EHIP;
+    size_t k = 0;
+    for (size_t i = 0; i < prof_.size(); ++i) {
+      ProfRec& r = prof_[i];
+      if ((int)r.kind != kind) {
+        prof_[k++] = r;
+        continue;
+      }
+      float t = 0.f;
+      if (chk(hipEventSynchronize(r.stop)) || chk(hipEventElapsedTime(&t, r.start, r.stop))) return MW_EHIP;
+      acc_[kind].launches += 1;
+      acc_[kind].ms += t;
+      acc_[kind].bytes += r.bytes;
+      prof_free_.push_back(r.start);
+      prof_free_.push_back(r.stop);
+    }
+    prof_.resize(k);
+    *launches = acc_[kind].launches;
+    *ms = acc_[kind].ms;
+    *bytes = acc_[kind].bytes;
+    acc_[kind] = ProfAcc{};
+    return MW_OK;
+  }
+
+ private:
+  static constexpr int kDepEvents = 256;
+
+  struct ProfRec {
+    uint32_t kind;
+    hipEvent_t start, stop;
+    uint64_t bytes;
+  };
+  struct ProfAcc {
+    uint64_t launches = 0;
+    double ms = 0;
+    uint64_t bytes = 0;
+  };
+
+  bool chk(hipError_t e) {
+    if (e == hipSuccess) return false;
+    last_err_ = (int)e;
+    return true;
+  }
+
+  hipEvent_t prof_event() {
+    if (!prof_free_.empty()) {
+      hipEvent_t e = prof_free_.back();
+      prof_free_.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    chk(hipEventCreate(&e));
+    return e;
+  }
+
+  uint32_t pick_chunk_shift(uint32_t kind, uint64_t total_bytes) const {
+    if (cfg_.chunk_bytes) return floor_log2(cfg_.chunk_bytes);
+    // enough workgroups to fill 256 CUs several times over, chunks large enough to amortise
+    // the per-chunk completion protocol
+    const uint32_t lo = kind == kReduce ? 12 : 14;   // 4 KiB / 16 KiB
+    const uint32_t hi = kind == kReduce ? 16 : 18;   // 64 KiB / 256 KiB
+    uint32_t s = floor_log2(total_bytes / 2048 + 1);
+    return std::min(hi, std::max(lo, s));
+  }
+
+  int launch_kind(uint32_t kind, const LaunchOp* ops, const int* idx, int n) {
+    uint64_t total_bytes = 0;
+    for (int i = 0; i < n; ++i) total_bytes += ops[idx[i]].nbytes;
+    const uint32_t shift = pick_chunk_shift(kind, total_bytes);
+    uint64_t chunks = 0;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (profiling_) {
+      e0 = prof_event();
+      e1 = prof_event();
+    }
+    if (kind == kCopy) {
+      CopyArgs& a = copy_args_;
+      a.n = (uint32_t)n;
+      a.chunk_shift = shift;
+      for (int i = 0; i < n; ++i) {
+        const LaunchOp& o = ops[idx[i]];
+        a.first_chunk[i] = (uint32_t)chunks;
+        chunks += (o.nbytes + (1ull << shift) - 1) >> shift;
+        a.e[i] = CopyEnt{o.buf[0], o.buf[1], o.nbytes, o.slot, o.gen, o.world_id, o.world_epoch};
+      }
+      a.first_chunk[n] = (uint32_t)chunks;
+      if (chunks == 0 || chunks > 0x7FFFFFFFull) return fail_inval();
+      if (profiling_ && chk(hipEventRecord(e0, data_))) return MW_EHIP;
+      hipLaunchKernelGGL(mw_k_copy, dim3((uint32_t)chunks), dim3(kCopyWG), 0, data_, a, slots_, flags_dev_);
+    } else {
+      CollArgs& a = coll_args_;
+      a.n = (uint32_t)n;
+      a.chunk_shift = shift;
+      for (int i = 0; i < n; ++i) {
+        const LaunchOp& o = ops[idx[i]];
+        a.first_chunk[i] = (uint32_t)chunks;
+        chunks += (o.nbytes + (1ull << shift) - 1) >> shift;
+        CollEnt& e = a.e[i];
+        for (int k = 0; k < kMaxBufs; ++k) e.buf[k] = k < (int)o.nbuf ? o.buf[k] : 0;
+        e.nbytes = o.nbytes;
+        e.slot = o.slot;
+        e.gen = o.gen;
+        e.nbuf = o.nbuf;
+        e.dtype = o.dtype;
+        e.world_id = o.world_id;
+        e.world_epoch = o.world_epoch;
+      }
+      a.first_chunk[n] = (uint32_t)chunks;
+      if (chunks == 0 || chunks > 0x7FFFFFFFull) return fail_inval();
+      if (profiling_ && chk(hipEventRecord(e0, data_))) return MW_EHIP;
+      if (kind == kBcast) {
+        hipLaunchKernelGGL(mw_k_bcast, dim3((uint32_t)chunks), dim3(kCopyWG), 0, data_, a, slots_, flags_dev_);
+      } else if (cfg_.reduce_lds) {
+        hipLaunchKernelGGL(mw_k_reduce<true>, dim3((uint32_t)chunks), dim3(kReduceWG), 0, data_, a, slots_,
+                           flags_dev_);
+      } else {
+        hipLaunchKernelGGL(mw_k_reduce<false>, dim3((uint32_t)chunks), dim3(kReduceWG), 0, data_, a, slots_,
+                           flags_dev_);
+      }
+    }
+    if (chk(hipGetLastError())) return MW_EHIP;
+    if (profiling_) {
+      if (chk(hipEventRecord(e1, data_))) return MW_EHIP;
+      prof_.push_back(ProfRec{kind, e0, e1, total_bytes});
+    }
+    return MW_OK;
+  }
+
+  int fail_inval() {
+    last_err_ = (int)hipErrorInvalidValue;
+    return MW_EHIP;
+  }
+
+  DeviceConfig cfg_{};
+  int dev_ = 0;
+  bool ready_ = false;
+  int last_err_ = 0;
+  void* arena_ = nullptr;
+  RingHeader* headers_ = nullptr;
+  RingSlot* slots_ = nullptr;
+  uint32_t* flags_host_ = nullptr;
+  uint32_t* flags_dev_ = nullptr;
+  hipStream_t data_ = nullptr, ctl_ = nullptr;
+  std::vector<hipEvent_t> dep_events_;
+  int dep_cursor_ = 0;
+  bool profiling_ = false;
+  std::vector<ProfRec> prof_;
+  std::vector<hipEvent_t> prof_free_;
+  ProfAcc acc_[kNumKinds];
+  std::vector<int> idx_;
+  CopyArgs copy_args_{};
+  CollArgs coll_args_{};
+};
+
+}  // namespace
+
+Device* make_device() { return new HipDevice(); }
+
+}  // namespace mw

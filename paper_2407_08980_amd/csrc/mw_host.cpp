@@ -1,0 +1,735 @@
+// Host runtime of the multi-world data plane: world table, matching of posted
+// sides, handles, ring-slot bookkeeping, abort and deferred ring release.
+//
+// Paper anchors (arXiv 2407.08980): worlds as fault domains and a worker in
+// many worlds (Sec. 3.1); non-blocking operations with polled status so that a
+// pending operation in one world never holds up another (Sec. 3.2); per-world
+// state kept side by side and looked up by key instead of being swapped in and
+// out (Sec. 3.2 "State management for multiple worlds"); fencing a broken world,
+// aborting its pending operations and raising to the caller (Sec. 3.3 "World
+// Manager").
+//
+// Nothing here touches payload bytes: all data movement is in the device backend.
+
+#include "../../include/mw.h"
+#include "mw_internal.hpp"
+
+#include <cstring>
+#include <deque>
+#include <memory>
+#include <mutex>
+#include <unordered_map>
+#include <vector>
+
+namespace mw {
+namespace {
+
+constexpr uint32_t kNone = 0xFFFFFFFFu;
+
+struct Post {  // one posted side that has not met its peers yet
+  uint32_t hslot;
+  uint64_t buf;
+  uint64_t count;
+  uint32_t dtype;
+  void* stream;
+};
+
+struct PairQ {
+  std::deque<Post> sends, recvs;
+};
+
+struct Coll {  // a collective some ranks have posted
+  int nposted = 0;
+  bool have[kMaxBufs] = {};
+  uint32_t kind[kMaxBufs] = {};
+  int root[kMaxBufs] = {};
+  Post post[kMaxBufs] = {};
+};
+
+struct World {
+  int id = 0;
+  std::vector<int> members;
+  int state = MW_ALIVE;
+  uint32_t epoch = 0;
+  uint32_t ring_index = kNone;
+  uint32_t first_slot = 0;
+  uint32_t depth = 0;
+  uint64_t free_mask = 0;  // bit i set: ring slot i is free
+  uint32_t queued = 0;     // operations with all sides posted, not launched yet
+  std::vector<uint32_t> inflight;  // op records launched and not yet seen complete
+  std::unordered_map<uint32_t, PairQ> pairs;  // key = src * MW_MAX_RANKS + dst
+  std::deque<Coll> coll;                      // coll[0] has sequence number coll_base
+  uint32_t coll_base = 0;
+  std::vector<uint32_t> coll_next;            // per rank: sequence number of its next collective
+  bool ring_released = false;
+};
+
+enum OpState : uint8_t { kOpFree = 0, kOpQueued = 1, kOpInflight = 2 };
+
+struct OpRec {  // an operation all of whose sides have been posted
+  LaunchOp l;
+  void* streams[kMaxBufs];
+  int n_streams;
+  uint32_t handles[kMaxBufs];
+  int n_handles;
+  uint32_t world;  // index into worlds
+  uint8_t state;
+};
+
+struct HandleEnt {
+  uint32_t gen = 0;
+  int32_t status = MW_DONE;  // a never-used entry counts as terminal: it can be allocated
+  uint32_t op = kNone;
+};
+
+struct Context {
+  std::unique_ptr<Device> dev;
+  int n_workers = 0;
+  DeviceConfig cfg{};
+  uint32_t max_rings = 1024;
+  uint32_t ring_depth = kMaxRingDepth;
+  bool frozen = false;  // geometry fixed once the first world exists
+
+  std::vector<std::unique_ptr<World>> worlds;
+  std::unordered_map<int, uint32_t> world_of_id;  // the key-value store of per-world state
+  std::vector<std::vector<uint32_t>> worlds_of_worker;
+  std::vector<uint32_t> free_rings;
+  std::vector<uint32_t> slot_gen;  // per arena slot: last generation handed out
+
+  std::vector<OpRec> ops;
+  std::vector<uint32_t> free_ops;
+  std::deque<uint32_t> ready;  // op records waiting for a launch, in match order
+
+  std::vector<HandleEnt> handles;
+  uint32_t handle_cursor = 0;
+
+  std::vector<LaunchOp> launch_buf;
+  std::vector<void*> stream_buf;
+  std::vector<uint32_t> launched_buf;
+};
+
+std::mutex g_lock;
+std::unique_ptr<Context> g_ctx;
+long g_cfg_chunk = 0, g_cfg_depth = kMaxRingDepth, g_cfg_lds = 0, g_cfg_rings = 1024, g_cfg_handles = 1 << 20;
+
+inline mw_handle make_handle(uint32_t slot, uint32_t gen) { return ((uint64_t)gen << 32) | slot; }
+
+// ---- handles ---------------------------------------------------------------------------------
+int alloc_handle(Context& c, uint32_t* out) {
+  const uint32_t cap = (uint32_t)c.handles.size();
+  for (uint32_t tries = 0; tries < cap; ++tries) {
+    uint32_t s = c.handle_cursor;
+    c.handle_cursor = (s + 1 == cap) ? 0 : s + 1;
+    HandleEnt& e = c.handles[s];
+    if (e.status == MW_PENDING) continue;  // still live: never recycle
+    e.gen += 1;
+    if (e.gen == 0) e.gen = 1;
+    e.status = MW_PENDING;
+    e.op = kNone;
+    *out = s;
+    return MW_OK;
+  }
+  return MW_ENOMEM;
+}
+
+inline void finish_handle(Context& c, uint32_t hslot, int status) {
+  HandleEnt& e = c.handles[hslot];
+  e.status = status;
+  e.op = kNone;
+}
+
+// ---- ring slots --------------------------------------------------------------------------------
+void release_ring_if_idle(Context& c, World& w) {
+  if (w.state == MW_BROKEN && !w.ring_released && w.queued == 0 && w.inflight.empty()) {
+    c.free_rings.push_back(w.ring_index);
+    w.ring_released = true;
+  }
+}
+
+void complete_op(Context& c, uint32_t opi) {
+  OpRec& op = c.ops[opi];
+  World& w = *c.worlds[op.world];
+  for (int i = 0; i < op.n_handles; ++i) finish_handle(c, op.handles[i], MW_DONE);
+  w.free_mask |= 1ull << (op.l.slot - w.first_slot);
+  op.state = kOpFree;
+  c.free_ops.push_back(opi);
+}
+
+// Look at the completion words of a world's in-flight operations; retire the finished ones.
+void retire_world(Context& c, World& w) {
+  size_t k = 0;
+  for (size_t i = 0; i < w.inflight.size(); ++i) {
+    uint32_t opi = w.inflight[i];
+    OpRec& op = c.ops[opi];
+    if (c.dev->flag(op.l.slot) == op.l.gen) {
+      complete_op(c, opi);
+    } else {
+      w.inflight[k++] = opi;
+    }
+  }
+  w.inflight.resize(k);
+  release_ring_if_idle(c, w);
+}
+
+void retire_one(Context& c, uint32_t opi) {
+  OpRec& op = c.ops[opi];
+  World& w = *c.worlds[op.world];
+  for (size_t i = 0; i < w.inflight.size(); ++i) {
+    if (w.inflight[i] == opi) {
+      w.inflight[i] = w.inflight.back();
+      w.inflight.pop_back();
+      break;
+    }
+  }
+  complete_op(c, opi);
+  release_ring_if_idle(c, w);
+}
+
+// ---- launching ---------------------------------------------------------------------------------
+int flush_locked(Context& c) {
+  if (c.ready.empty()) return MW_OK;
+  c.launch_buf.clear();
+  c.stream_buf.clear();
+  c.launched_buf.clear();
+  std::deque<uint32_t> deferred;
+  while (!c.ready.empty()) {
+    uint32_t opi = c.ready.front();
+    c.ready.pop_front();
+    OpRec& op = c.ops[opi];
+    World& w = *c.worlds[op.world];
+    if (w.free_mask == 0) retire_world(c, w);
+    if (w.free_mask == 0) {  // ring full: stays queued until earlier operations retire
+      deferred.push_back(opi);
+      continue;
+    }
+    uint32_t bit = (uint32_t)__builtin_ctzll(w.free_mask);
+    w.free_mask &= ~(1ull << bit);
+    uint32_t slot = w.first_slot + bit;
+    uint32_t gen = c.slot_gen[slot] + 1;
+    if (gen == 0) gen = 1;
+    c.slot_gen[slot] = gen;
+    op.l.slot = slot;
+    op.l.gen = gen;
+    op.l.world_epoch = w.epoch;
+    c.launch_buf.push_back(op.l);
+    c.launched_buf.push_back(opi);
+    for (int i = 0; i < op.n_streams; ++i) {
+      void* s = op.streams[i];
+      bool seen = false;
+      for (void* t : c.stream_buf) seen |= (t == s);
+      if (!seen) c.stream_buf.push_back(s);
+    }
+  }
+  c.ready.swap(deferred);
+  if (c.launch_buf.empty()) return MW_OK;
+  int rc = c.dev->launch(c.launch_buf.data(), (int)c.launch_buf.size(), c.stream_buf.data(),
+                         (int)c.stream_buf.size());
+  if (rc != MW_OK) {
+    // Nothing was enqueued for these operations: put them back, slots freed.
+    for (size_t i = c.launched_buf.size(); i-- > 0;) {
+      OpRec& op = c.ops[c.launched_buf[i]];
+      World& w = *c.worlds[op.world];
+      w.free_mask |= 1ull << (op.l.slot - w.first_slot);
+      c.ready.push_front(c.launched_buf[i]);
+    }
+    return rc;
+  }
+  for (uint32_t opi : c.launched_buf) {
+    OpRec& op = c.ops[opi];
+    World& w = *c.worlds[op.world];
+    op.state = kOpInflight;
+    w.queued -= 1;
+    w.inflight.push_back(opi);
+  }
+  return MW_OK;
+}
+
+// An operation with all sides present: give it a record and queue it for the next launch.
+int enqueue_op(Context& c, uint32_t wi, uint32_t kind, uint32_t dtype, uint64_t nbytes, const Post* posts,
+               int n_posts, const int* buf_order) {
+  uint32_t opi;
+  if (!c.free_ops.empty()) {
+    opi = c.free_ops.back();
+    c.free_ops.pop_back();
+  } else {
+    opi = (uint32_t)c.ops.size();
+    c.ops.emplace_back();
+  }
+  OpRec& op = c.ops[opi];
+  std::memset(&op, 0, sizeof(op));
+  op.world = wi;
+  op.state = kOpQueued;
+  op.l.kind = kind;
+  op.l.dtype = dtype;
+  op.l.nbytes = nbytes;
+  op.l.nbuf = (uint32_t)n_posts;
+  op.l.world_id = (uint32_t)c.worlds[wi]->id;
+  for (int i = 0; i < n_posts; ++i) {
+    const Post& p = posts[buf_order[i]];
+    op.l.buf[i] = p.buf;
+    op.handles[op.n_handles++] = p.hslot;
+    c.handles[p.hslot].op = opi;
+    if (p.stream != MW_STREAM_NONE) {
+      bool seen = false;
+      for (int k = 0; k < op.n_streams; ++k) seen |= (op.streams[k] == p.stream);
+      if (!seen) op.streams[op.n_streams++] = p.stream;
+    }
+  }
+  c.worlds[wi]->queued += 1;
+  c.ready.push_back(opi);
+  return MW_OK;
+}
+
+inline uint64_t item_size(uint32_t dtype) { return dtype == MW_F32 ? 4 : 2; }
+
+// ---- posting -----------------------------------------------------------------------------------
+int post_p2p(bool is_send, int world_id, int src, int dst, const void* buf, size_t count, mw_dtype dtype,
+             void* stream, mw_handle* out) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  Context& c = *g_ctx;
+  if (!out || (dtype != MW_F32 && dtype != MW_BF16)) return MW_EINVAL;
+  auto it = c.world_of_id.find(world_id);
+  if (it == c.world_of_id.end()) return MW_ENOWORLD;
+  World& w = *c.worlds[it->second];
+  const int n = (int)w.members.size();
+  if (src < 0 || dst < 0 || src >= n || dst >= n || src == dst) return MW_EINVAL;
+  if (count > 0 && !buf) return MW_EINVAL;
+  if (count > (SIZE_MAX >> 3)) return MW_EINVAL;
+  if (w.state == MW_BROKEN) return MW_EBROKEN;
+  uint32_t hs;
+  int rc = alloc_handle(c, &hs);
+  if (rc != MW_OK) return rc;
+  *out = make_handle(hs, c.handles[hs].gen);
+  Post me{hs, (uint64_t)(uintptr_t)buf, (uint64_t)count, (uint32_t)dtype, stream};
+  PairQ& q = w.pairs[(uint32_t)src * MW_MAX_RANKS + (uint32_t)dst];
+  std::deque<Post>& theirs = is_send ? q.recvs : q.sends;
+  if (theirs.empty()) {
+    (is_send ? q.sends : q.recvs).push_back(me);
+    return MW_OK;
+  }
+  Post other = theirs.front();
+  theirs.pop_front();
+  if (other.count != me.count || other.dtype != me.dtype) {
+    finish_handle(c, hs, MW_EMISMATCH);
+    finish_handle(c, other.hslot, MW_EMISMATCH);
+    return MW_OK;
+  }
+  if (count == 0) {
+    finish_handle(c, hs, MW_DONE);
+    finish_handle(c, other.hslot, MW_DONE);
+    return MW_OK;
+  }
+  Post pair[2] = {is_send ? me : other, is_send ? other : me};  // {send side, recv side}
+  const int order[2] = {0, 1};
+  return enqueue_op(c, it->second, kCopy, (uint32_t)dtype, count * item_size(dtype), pair, 2, order);
+}
+
+int post_coll(uint32_t kind, int world_id, int rank, int root, void* buf, size_t count, mw_dtype dtype,
+              void* stream, mw_handle* out) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  Context& c = *g_ctx;
+  if (!out || (dtype != MW_F32 && dtype != MW_BF16)) return MW_EINVAL;
+  auto it = c.world_of_id.find(world_id);
+  if (it == c.world_of_id.end()) return MW_ENOWORLD;
+  World& w = *c.worlds[it->second];
+  const int n = (int)w.members.size();
+  if (n > MW_MAX_COLL_RANKS) return MW_EINVAL;
+  if (rank < 0 || rank >= n) return MW_EINVAL;
+  if (kind == kBcast && (root < 0 || root >= n)) return MW_EINVAL;
+  if (count > 0 && !buf) return MW_EINVAL;
+  if (kind == kReduce && ((uintptr_t)buf % item_size(dtype)) != 0) return MW_EINVAL;  // elements are loaded whole
+  if (count > (SIZE_MAX >> 3)) return MW_EINVAL;
+  if (w.state == MW_BROKEN) return MW_EBROKEN;
+  uint32_t hs;
+  int rc = alloc_handle(c, &hs);
+  if (rc != MW_OK) return rc;
+  *out = make_handle(hs, c.handles[hs].gen);
+  uint32_t seq = w.coll_next[rank]++;
+  uint32_t idx = seq - w.coll_base;
+  while (w.coll.size() <= idx) w.coll.emplace_back();
+  Coll& cl = w.coll[idx];
+  cl.have[rank] = true;
+  cl.kind[rank] = kind;
+  cl.root[rank] = (kind == kBcast) ? root : 0;
+  cl.post[rank] = Post{hs, (uint64_t)(uintptr_t)buf, (uint64_t)count, (uint32_t)dtype, stream};
+  cl.nposted += 1;
+  // A world's collectives run in sequence order, each as soon as all its ranks have posted.
+  while (!w.coll.empty() && w.coll.front().nposted == n) {
+    Coll f = w.coll.front();
+    w.coll.pop_front();
+    w.coll_base += 1;
+    bool same = true;
+    for (int r = 1; r < n; ++r) {
+      same &= f.kind[r] == f.kind[0] && f.root[r] == f.root[0] && f.post[r].count == f.post[0].count &&
+              f.post[r].dtype == f.post[0].dtype;
+    }
+    if (!same) {
+      for (int r = 0; r < n; ++r) finish_handle(c, f.post[r].hslot, MW_EMISMATCH);
+      continue;
+    }
+    if (f.post[0].count == 0 || n == 1) {  // nothing to move
+      for (int r = 0; r < n; ++r) finish_handle(c, f.post[r].hslot, MW_DONE);
+      continue;
+    }
+    int order[kMaxBufs];
+    int k = 0;
+    if (f.kind[0] == kBcast) {  // descriptor order: root first, then the other ranks ascending
+      order[k++] = f.root[0];
+      for (int r = 0; r < n; ++r)
+        if (r != f.root[0]) order[k++] = r;
+    } else {
+      for (int r = 0; r < n; ++r) order[k++] = r;
+    }
+    rc = enqueue_op(c, it->second, f.kind[0], f.post[0].dtype, f.post[0].count * item_size(f.post[0].dtype),
+                    f.post, n, order);
+    if (rc != MW_OK) return rc;
+  }
+  return MW_OK;
+}
+
+int abort_world_locked(Context& c, World& w) {
+  if (w.state == MW_BROKEN) return MW_OK;
+  w.state = MW_BROKEN;
+  w.epoch += 1;
+  for (auto& kv : w.pairs) {
+    for (const Post& p : kv.second.sends) finish_handle(c, p.hslot, MW_BROKEN);
+    for (const Post& p : kv.second.recvs) finish_handle(c, p.hslot, MW_BROKEN);
+  }
+  w.pairs.clear();
+  for (const Coll& cl : w.coll)
+    for (int r = 0; r < kMaxBufs; ++r)
+      if (cl.have[r]) finish_handle(c, cl.post[r].hslot, MW_BROKEN);
+  w.coll.clear();
+  RingHeader h{};
+  h.world_id = (uint32_t)w.id;
+  h.state = MW_BROKEN;
+  h.epoch = w.epoch;
+  h.depth = w.depth;
+  h.first_slot = w.first_slot;
+  h.n_ranks = (uint32_t)w.members.size();
+  int rc = c.dev->mark_world(w.ring_index, h);
+  // Operations that already had all their sides are delivered: launch them now so that they retire.
+  int rc2 = flush_locked(c);
+  retire_world(c, w);
+  return rc != MW_OK ? rc : rc2;
+}
+
+int poll_locked(Context& c, mw_handle h) {
+  uint32_t slot = (uint32_t)(h & 0xFFFFFFFFu), gen = (uint32_t)(h >> 32);
+  if (slot >= c.handles.size() || gen == 0) return MW_EBADHANDLE;
+  HandleEnt& e = c.handles[slot];
+  if (e.gen != gen) return MW_EBADHANDLE;
+  if (e.status != MW_PENDING) return e.status;
+  if (e.op == kNone) return MW_PENDING;  // still waiting for a peer
+  uint32_t opi = e.op;
+  if (c.ops[opi].state == kOpQueued) {
+    int rc = flush_locked(c);
+    if (rc != MW_OK) return rc;
+  }
+  OpRec& op = c.ops[opi];
+  if (op.state == kOpInflight && c.dev->flag(op.l.slot) == op.l.gen) {
+    retire_one(c, opi);
+    return MW_DONE;
+  }
+  return MW_PENDING;
+}
+
+}  // namespace
+}  // namespace mw
+
+using namespace mw;
+
+extern "C" {
+
+int mw_init(int hip_device, int n_workers) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (g_ctx || n_workers < 1) return MW_EINVAL;
+  std::unique_ptr<Context> c(new Context());
+  c->n_workers = n_workers;
+  c->max_rings = (uint32_t)g_cfg_rings;
+  c->ring_depth = (uint32_t)g_cfg_depth;
+  c->cfg.total_rings = c->max_rings;
+  c->cfg.total_slots = c->max_rings * c->ring_depth;
+  c->cfg.chunk_bytes = (uint32_t)g_cfg_chunk;
+  c->cfg.reduce_lds = (uint32_t)g_cfg_lds;
+  c->dev.reset(make_device());
+  int rc = c->dev->init(hip_device, c->cfg);
+  if (rc != MW_OK) return rc;
+  c->worlds_of_worker.resize((size_t)n_workers);
+  c->slot_gen.assign(c->cfg.total_slots, 0);
+  for (uint32_t r = c->max_rings; r-- > 0;) c->free_rings.push_back(r);
+  c->handles.resize((size_t)g_cfg_handles);
+  g_ctx = std::move(c);
+  return MW_OK;
+}
+
+int mw_shutdown(void) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  flush_locked(*g_ctx);
+  g_ctx->dev->sync();
+  g_ctx->dev->shutdown();
+  g_ctx.reset();
+  return MW_OK;
+}
+
+int mw_world_create(int world_id, const int* worker_ids, int n_ranks) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  Context& c = *g_ctx;
+  if (!worker_ids || n_ranks < 1 || n_ranks > MW_MAX_RANKS) return MW_EINVAL;
+  for (int i = 0; i < n_ranks; ++i) {
+    if (worker_ids[i] < 0 || worker_ids[i] >= c.n_workers) return MW_EINVAL;
+    for (int j = 0; j < i; ++j)
+      if (worker_ids[j] == worker_ids[i]) return MW_EINVAL;
+  }
+  if (c.world_of_id.count(world_id)) return MW_EEXIST;
+  if (c.free_rings.empty()) {  // rings of broken worlds come back once their operations retired
+    for (auto& wp : c.worlds)
+      if (wp->state == MW_BROKEN && !wp->ring_released) retire_world(c, *wp);
+    if (c.free_rings.empty()) return MW_ENOMEM;
+  }
+  std::unique_ptr<World> w(new World());
+  w->id = world_id;
+  w->members.assign(worker_ids, worker_ids + n_ranks);
+  w->ring_index = c.free_rings.back();
+  c.free_rings.pop_back();
+  w->depth = c.ring_depth;
+  w->first_slot = w->ring_index * c.ring_depth;
+  w->free_mask = w->depth == 64 ? ~0ull : ((1ull << w->depth) - 1);
+  w->coll_next.assign((size_t)n_ranks, 0);
+  RingHeader h{};
+  h.world_id = (uint32_t)world_id;
+  h.state = MW_ALIVE;
+  h.epoch = 0;
+  h.depth = w->depth;
+  h.first_slot = w->first_slot;
+  h.n_ranks = (uint32_t)n_ranks;
+  int rc = c.dev->mark_world(w->ring_index, h);
+  if (rc != MW_OK) {
+    c.free_rings.push_back(w->ring_index);
+    return rc;
+  }
+  uint32_t wi = (uint32_t)c.worlds.size();
+  for (int i = 0; i < n_ranks; ++i) c.worlds_of_worker[(size_t)worker_ids[i]].push_back(wi);
+  c.world_of_id.emplace(world_id, wi);
+  c.worlds.push_back(std::move(w));
+  c.frozen = true;
+  return MW_OK;
+}
+
+int mw_world_abort(int world_id) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  auto it = g_ctx->world_of_id.find(world_id);
+  if (it == g_ctx->world_of_id.end()) return MW_ENOWORLD;
+  return abort_world_locked(*g_ctx, *g_ctx->worlds[it->second]);
+}
+
+int mw_worker_abort(int worker_id) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  Context& c = *g_ctx;
+  if (worker_id < 0 || worker_id >= c.n_workers) return MW_EINVAL;
+  int rc = MW_OK;
+  for (uint32_t wi : c.worlds_of_worker[(size_t)worker_id]) {
+    int r = abort_world_locked(c, *c.worlds[wi]);
+    if (r != MW_OK) rc = r;
+  }
+  return rc;
+}
+
+int mw_world_state(int world_id) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  auto it = g_ctx->world_of_id.find(world_id);
+  if (it == g_ctx->world_of_id.end()) return MW_ENOWORLD;
+  return g_ctx->worlds[it->second]->state;
+}
+
+int mw_send(int world_id, int src_rank, int dst_rank, const void* buf, size_t count, mw_dtype dtype,
+            void* hip_stream, mw_handle* out) {
+  return post_p2p(true, world_id, src_rank, dst_rank, buf, count, dtype, hip_stream, out);
+}
+
+int mw_recv(int world_id, int src_rank, int dst_rank, void* buf, size_t count, mw_dtype dtype, void* hip_stream,
+            mw_handle* out) {
+  return post_p2p(false, world_id, src_rank, dst_rank, buf, count, dtype, hip_stream, out);
+}
+
+int mw_broadcast(int world_id, int rank, int root_rank, void* buf, size_t count, mw_dtype dtype,
+                 void* hip_stream, mw_handle* out) {
+  return post_coll(kBcast, world_id, rank, root_rank, buf, count, dtype, hip_stream, out);
+}
+
+int mw_allreduce_sum(int world_id, int rank, void* buf, size_t count, mw_dtype dtype, void* hip_stream,
+                     mw_handle* out) {
+  return post_coll(kReduce, world_id, rank, 0, buf, count, dtype, hip_stream, out);
+}
+
+int mw_poll(mw_handle h) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  return poll_locked(*g_ctx, h);
+}
+
+int mw_poll_many(const mw_handle* handles, int n, int* states) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  if (n < 0 || (n > 0 && (!handles || !states))) return MW_EINVAL;
+  int pending = 0;
+  for (int i = 0; i < n; ++i) {
+    states[i] = poll_locked(*g_ctx, handles[i]);
+    pending += states[i] == MW_PENDING;
+  }
+  return pending;
+}
+
+int mw_pending_ops(void) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  int n = 0;
+  for (auto& w : g_ctx->worlds) n += (int)w->queued + (int)w->inflight.size();
+  return n;
+}
+
+int mw_flush(void) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  return flush_locked(*g_ctx);
+}
+
+int mw_config_set(const char* key, long value) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!key) return MW_EINVAL;
+  const bool live = (bool)g_ctx;
+  if (!std::strcmp(key, "chunk_bytes")) {
+    if (value != 0 && (value < 4096 || value > 4194304 || (value & (value - 1)))) return MW_EINVAL;
+    g_cfg_chunk = value;
+    if (live) {
+      g_ctx->cfg.chunk_bytes = (uint32_t)value;
+      g_ctx->dev->set_config(g_ctx->cfg);
+    }
+    return MW_OK;
+  }
+  if (!std::strcmp(key, "reduce_lds")) {
+    if (value != 0 && value != 1) return MW_EINVAL;
+    g_cfg_lds = value;
+    if (live) {
+      g_ctx->cfg.reduce_lds = (uint32_t)value;
+      g_ctx->dev->set_config(g_ctx->cfg);
+    }
+    return MW_OK;
+  }
+  // geometry: only before mw_init
+  if (live) return MW_EINVAL;
+  if (!std::strcmp(key, "ring_depth")) {
+    if (value < 1 || value > kMaxRingDepth) return MW_EINVAL;
+    g_cfg_depth = value;
+    return MW_OK;
+  }
+  if (!std::strcmp(key, "max_rings")) {
+    if (value < 1 || value > 65536) return MW_EINVAL;
+    g_cfg_rings = value;
+    return MW_OK;
+  }
+  if (!std::strcmp(key, "handle_capacity")) {
+    if (value < 16 || value > (1l << 26)) return MW_EINVAL;
+    g_cfg_handles = value;
+    return MW_OK;
+  }
+  return MW_EINVAL;
+}
+
+long mw_config_get(const char* key) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!key) return MW_EINVAL;
+  if (!std::strcmp(key, "chunk_bytes")) return g_cfg_chunk;
+  if (!std::strcmp(key, "reduce_lds")) return g_cfg_lds;
+  if (!std::strcmp(key, "ring_depth")) return g_cfg_depth;
+  if (!std::strcmp(key, "max_rings")) return g_cfg_rings;
+  if (!std::strcmp(key, "handle_capacity")) return g_cfg_handles;
+  return MW_EINVAL;
+}
+
+int mw_handle_capacity(void) {
+  std::lock_guard<std::mutex> g(g_lock);
+  return g_ctx ? (int)g_ctx->handles.size() : (int)g_cfg_handles;
+}
+
+int mw_last_hip_error(void) {
+  std::lock_guard<std::mutex> g(g_lock);
+  return g_ctx ? g_ctx->dev->last_hip_error() : 0;
+}
+
+const char* mw_strerror(int err) {
+  switch (err) {
+    case MW_OK: return "ok";
+    case MW_EINVAL: return "invalid argument";
+    case MW_ENOWORLD: return "no such world";
+    case MW_EBROKEN: return "world is broken";
+    case MW_EEXIST: return "world id already used";
+    case MW_EMISMATCH: return "sides of the operation disagree";
+    case MW_ENOMEM: return "library table full";
+    case MW_EBADHANDLE: return "bad or recycled handle";
+    case MW_EHIP: return "HIP call failed";
+    case MW_ENOTINIT: return "mw_init not called";
+    default: return "unknown error";
+  }
+}
+
+int mw_profile_enable(int on) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  return g_ctx->dev->profile_enable(on);
+}
+
+int mw_profile_read(int kind, uint64_t* launches, double* total_ms, uint64_t* op_bytes) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  if (kind < 0 || kind >= (int)kNumKinds || !launches || !total_ms || !op_bytes) return MW_EINVAL;
+  return g_ctx->dev->profile_read(kind, launches, total_ms, op_bytes);
+}
+
+long mw_debug_ring_read(int world_id, void* out, size_t cap) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  Context& c = *g_ctx;
+  auto it = c.world_of_id.find(world_id);
+  if (it == c.world_of_id.end()) return MW_ENOWORLD;
+  World& w = *c.worlds[it->second];
+  size_t need = (size_t)kHeaderBytes + (size_t)w.depth * kSlotBytes;
+  if (!out || cap < need) return MW_EINVAL;
+  int rc = c.dev->read_ring(w.ring_index, w.first_slot, w.depth, out);
+  return rc == MW_OK ? (long)need : rc;
+}
+
+int mw_debug_arena_hash(int except_world, uint64_t* hash) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  Context& c = *g_ctx;
+  if (!hash) return MW_EINVAL;
+  uint32_t skip = kNone;
+  if (except_world != -1) {
+    auto it = c.world_of_id.find(except_world);
+    if (it == c.world_of_id.end()) return MW_ENOWORLD;
+    skip = c.worlds[it->second]->ring_index;
+  }
+  std::vector<unsigned char> tmp((size_t)kHeaderBytes + (size_t)c.ring_depth * kSlotBytes);
+  uint64_t hsh = 1469598103934665603ull;
+  for (uint32_t r = 0; r < c.max_rings; ++r) {
+    if (r == skip) continue;
+    int rc = c.dev->read_ring(r, r * c.ring_depth, c.ring_depth, tmp.data());
+    if (rc != MW_OK) return rc;
+    for (unsigned char b : tmp) {
+      hsh ^= b;
+      hsh *= 1099511628211ull;
+    }
+  }
+  *hash = hsh;
+  return MW_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,107 @@
+// Internal contract between the host runtime (mw_host.cpp) and a device backend.
+//
+// The host runtime owns the world table, matching, handles and ring-slot
+// bookkeeping.  A backend owns device memory and launches.  The real backend
+// is mw_device.hip; mw_device_null.cpp is a test double that moves no bytes
+// and lets the host state machine be exercised without a GPU.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+
+namespace mw {
+
+constexpr int kMaxBufs = 8;          // buffers named by one descriptor (== MW_MAX_COLL_RANKS)
+constexpr int kSlotBytes = 256;      // one ring slot in HBM
+constexpr int kHeaderBytes = 256;    // one ring header in HBM
+constexpr int kMaxRingDepth = 64;
+
+enum Kind : uint32_t { kCopy = 0, kBcast = 1, kReduce = 2, kNumKinds = 3 };
+
+// Journal half of a ring slot (first 128 bytes): the descriptor of the operation
+// occupying the slot, written by the GPU when the operation is dispatched.
+struct SlotDesc {
+  uint64_t buf[kMaxBufs];  // copy: {src, dst}; bcast: {root, dst...}; reduce: all ranks' buffers
+  uint64_t nbytes;
+  uint32_t kind;
+  uint32_t dtype;
+  uint32_t nbuf;
+  uint32_t world_id;
+  uint32_t world_epoch;
+  uint32_t gen;       // completion generation this operation publishes
+  uint32_t nchunks;
+  uint32_t chunk_bytes;
+  uint32_t pad[6];
+};
+static_assert(sizeof(SlotDesc) == 128, "journal half is 128 bytes");
+
+// Sync half of a ring slot (second 128 bytes): touched only by device atomics.
+struct SlotSync {
+  uint32_t arrived;   // chunks retired so far; the last one resets it to 0
+  uint32_t done_gen;  // generation of the last operation completed in this slot
+  uint32_t pad[30];
+};
+static_assert(sizeof(SlotSync) == 128, "sync half is 128 bytes");
+
+struct RingSlot {
+  SlotDesc d;
+  SlotSync s;
+};
+static_assert(sizeof(RingSlot) == kSlotBytes, "ring slot size");
+
+// Ring header in HBM, written by the world-marker kernel at create and abort.
+struct RingHeader {
+  uint32_t world_id;
+  uint32_t state;   // 0 alive, 2 broken
+  uint32_t epoch;   // bumped by every marker write
+  uint32_t depth;
+  uint32_t first_slot;  // global index of the ring's first slot
+  uint32_t n_ranks;
+  uint32_t pad[58];
+};
+static_assert(sizeof(RingHeader) == kHeaderBytes, "ring header size");
+
+// One operation handed to a launch.
+struct LaunchOp {
+  uint64_t buf[kMaxBufs];
+  uint64_t nbytes;
+  uint32_t kind;
+  uint32_t dtype;
+  uint32_t nbuf;
+  uint32_t slot;   // global ring slot index
+  uint32_t gen;
+  uint32_t world_id;
+  uint32_t world_epoch;
+};
+
+struct DeviceConfig {
+  uint32_t total_slots;   // ring slots in the arena
+  uint32_t total_rings;   // ring headers in the arena
+  uint32_t chunk_bytes;   // 0 = choose per launch
+  uint32_t reduce_lds;    // stage all-reduce tiles through LDS
+};
+
+class Device {
+ public:
+  virtual ~Device() {}
+  virtual int init(int hip_device, const DeviceConfig& cfg) = 0;
+  virtual void shutdown() = 0;
+  virtual void set_config(const DeviceConfig& cfg) = 0;
+  // Launch `n` operations (any mix of kinds, any worlds), ordered after the work already
+  // enqueued on each of `streams` (hipStream_t as void*, NULL = null stream).  Returns 0 or MW_EHIP.
+  virtual int launch(const LaunchOp* ops, int n, void* const* streams, int n_streams) = 0;
+  // Write a ring header (world create / abort marker).  Asynchronous, on the library's stream.
+  virtual int mark_world(uint32_t ring_index, const RingHeader& h) = 0;
+  // Host-visible completion word of a slot (acquire load of the pinned mirror).
+  virtual uint32_t flag(uint32_t slot) = 0;
+  // Diagnostics: block until idle, then copy arena bytes to the host.
+  virtual int read_ring(uint32_t ring_index, uint32_t first_slot, uint32_t depth, void* out) = 0;
+  virtual int sync() = 0;
+  virtual int last_hip_error() = 0;
+  virtual int profile_enable(int on) = 0;
+  virtual int profile_read(int kind, uint64_t* launches, double* ms, uint64_t* bytes) = 0;
+};
+
+Device* make_device();  // provided by exactly one backend per library
+
+}  // namespace mw
