@@ -1,0 +1,342 @@
+"""Host runtime on the CPU: matching, handles, ring slots, abort, deferred ring release.
+
+These tests link the host runtime against a device test double that records
+launches and moves no bytes (libmw_hostcheck.so); the test decides when launched
+operations "complete".  The product library is also loaded to check that it exports
+every symbol the header declares (no compute calls: there is no GPU here).
+"""
+
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2407_08980_amd import binding as mw
+from paper_2407_08980_amd import build as mwbuild
+
+from helpers import ROOT
+
+
+@pytest.fixture(scope="module")
+def hostlib():
+    if not os.path.exists(mwbuild.LIB_HOSTCHECK):
+        mwbuild.build_hostcheck()
+    lib = C.CDLL(mwbuild.LIB_HOSTCHECK)
+    lib.mwt_log_entry.argtypes = [C.c_int, C.POINTER(C.c_uint64)]
+    old = mw._lib
+    mw.use_library(lib)
+    yield lib
+    mw._lib = old
+
+
+@pytest.fixture
+def ctx(hostlib):
+    mw.mw_init(0, 8)
+    yield hostlib
+    mw.mw_shutdown()
+
+
+def log_entry(lib, i):
+    out = (C.c_uint64 * 17)()
+    assert lib.mwt_log_entry(i, out) == 0
+    return dict(buf=list(out[:8]), nbytes=out[8], kind=out[9], dtype=out[10], nbuf=out[11], slot=out[12],
+                gen=out[13], world=out[14], epoch=out[15], launch=out[16])
+
+
+def test_header_symbols_are_exported_by_the_product_library():
+    if not os.path.exists(mw.LIB_PATH):
+        mwbuild.build_product()
+    text = open(os.path.join(ROOT, "include", "mw.h")).read()
+    declared = set(re.findall(r"^\s*(?:int|long|const char\*)\s+(mw_\w+)\s*\(", text, flags=re.M))
+    assert {"mw_world_create", "mw_send", "mw_recv", "mw_broadcast", "mw_allreduce_sum", "mw_poll",
+            "mw_world_abort"} <= declared
+    lib = C.CDLL(mw.LIB_PATH)
+    missing = [s for s in sorted(declared) if not hasattr(lib, s)]
+    assert not missing, missing
+    assert declared == set(mw.SYMBOLS), declared ^ set(mw.SYMBOLS)
+    # without a GPU the library must refuse loudly, not fall back
+    import torch
+
+    if not torch.cuda.is_available():
+        lib.mw_init.argtypes = [C.c_int, C.c_int]
+        assert lib.mw_init(0, 2) == mw.MW_EHIP
+        assert lib.mw_poll(C.c_uint64(1 << 32)) == mw.MW_ENOTINIT
+
+
+def test_calls_before_init_are_refused(hostlib):
+    assert hostlib.mw_flush() == mw.MW_ENOTINIT
+    assert hostlib.mw_poll(C.c_uint64(1 << 32)) == mw.MW_ENOTINIT
+    with pytest.raises(mw.MwError) as e:
+        mw.mw_world_create(0, [0, 1])
+    assert e.value.code == mw.MW_ENOTINIT
+
+
+def test_rendezvous_matching_and_batched_launch(ctx):
+    mw.mw_world_create(5, [0, 1])
+    mw.mw_world_create(6, [0, 2])
+    hs = mw.mw_send(5, 1, 0, 0x1000, 100, mw.MW_F32)
+    assert mw.mw_poll(hs) == mw.MW_PENDING and ctx.mwt_launch_count() == 0  # no receiver yet: nothing launched
+    hr = mw.mw_recv(5, 1, 0, 0x2000, 100, mw.MW_F32)
+    h2r = mw.mw_recv(6, 1, 0, 0x4000, 7, mw.MW_BF16)
+    h2s = mw.mw_send(6, 1, 0, 0x3000, 7, mw.MW_BF16)
+    assert mw.mw_pending_ops() == 2 and ctx.mwt_launch_count() == 0
+    mw.mw_flush()
+    assert ctx.mwt_launch_count() == 1 and ctx.mwt_launch_size(0) == 2  # one launch covers both worlds
+    a, b = log_entry(ctx, 0), log_entry(ctx, 1)
+    assert (a["buf"][:2], a["nbytes"], a["kind"], a["world"]) == ([0x1000, 0x2000], 400, 0, 5)
+    assert (b["buf"][:2], b["nbytes"], b["kind"], b["world"]) == ([0x3000, 0x4000], 14, 0, 6)
+    assert a["slot"] // 64 != b["slot"] // 64  # each world has its own ring
+    assert [mw.mw_poll(h) for h in (hs, hr, h2s, h2r)] == [mw.MW_PENDING] * 4
+    ctx.mwt_complete(1, 0)
+    assert [mw.mw_poll(h) for h in (hs, hr, h2s, h2r)] == [mw.MW_DONE, mw.MW_DONE, mw.MW_PENDING, mw.MW_PENDING]
+    ctx.mwt_complete(1, 0)
+    assert mw.mw_poll(h2r) == mw.MW_DONE and mw.mw_poll(h2s) == mw.MW_DONE and mw.mw_pending_ops() == 0
+    assert mw.mw_poll(hs) == mw.MW_DONE  # sticky
+
+
+def test_poll_launches_on_demand(ctx):
+    mw.mw_world_create(0, [0, 1])
+    hs = mw.mw_send(0, 0, 1, 0x10, 4, mw.MW_F32)
+    hr = mw.mw_recv(0, 0, 1, 0x20, 4, mw.MW_F32)
+    assert ctx.mwt_launch_count() == 0
+    assert mw.mw_poll(hr) == mw.MW_PENDING and ctx.mwt_launch_count() == 1
+    ctx.mwt_complete(1, 0)
+    assert mw.mw_poll(hs) == mw.MW_DONE
+
+
+def test_fifo_per_pair_and_no_crosstalk(ctx):
+    mw.mw_world_create(0, [0, 1, 2])
+    sends = [mw.mw_send(0, 1, 0, 0x1000 + 16 * k, 1, mw.MW_F32) for k in range(5)]
+    other = mw.mw_send(0, 2, 0, 0x9000, 1, mw.MW_F32)
+    recvs = [mw.mw_recv(0, 1, 0, 0x2000 + 16 * k, 1, mw.MW_F32) for k in range(5)]
+    mw.mw_flush()
+    assert ctx.mwt_log_size() == 5
+    for k in range(5):
+        assert log_entry(ctx, k)["buf"][:2] == [0x1000 + 16 * k, 0x2000 + 16 * k]
+    assert mw.mw_poll(other) == mw.MW_PENDING
+
+
+def test_mismatch_and_zero_count(ctx):
+    mw.mw_world_create(0, [0, 1])
+    hs = mw.mw_send(0, 0, 1, 0x10, 8, mw.MW_F32)
+    hr = mw.mw_recv(0, 0, 1, 0x20, 4, mw.MW_F32)
+    assert mw.mw_poll(hs) == mw.MW_EMISMATCH and mw.mw_poll(hr) == mw.MW_EMISMATCH
+    hs = mw.mw_send(0, 0, 1, 0x10, 8, mw.MW_BF16)
+    hr = mw.mw_recv(0, 0, 1, 0x20, 8, mw.MW_F32)
+    assert mw.mw_poll(hs) == mw.MW_EMISMATCH and mw.mw_poll(hr) == mw.MW_EMISMATCH
+    hs = mw.mw_send(0, 0, 1, 0, 0, mw.MW_F32)
+    hr = mw.mw_recv(0, 0, 1, 0, 0, mw.MW_F32)
+    assert mw.mw_poll(hs) == mw.MW_DONE and mw.mw_poll(hr) == mw.MW_DONE
+    assert ctx.mwt_launch_count() == 0
+
+
+def test_argument_errors(ctx):
+    mw.mw_world_create(0, [0, 1])
+    for args, code in [((0, 0, 0, 0x10, 1), mw.MW_EINVAL), ((0, 0, 2, 0x10, 1), mw.MW_EINVAL),
+                       ((0, -1, 1, 0x10, 1), mw.MW_EINVAL), ((9, 0, 1, 0x10, 1), mw.MW_ENOWORLD),
+                       ((0, 0, 1, 0, 1), mw.MW_EINVAL)]:
+        with pytest.raises(mw.MwError) as e:
+            mw.mw_send(*args, mw.MW_F32)
+        assert e.value.code == code
+    for members, code in [([0, 0], mw.MW_EINVAL), ([0, 8], mw.MW_EINVAL), ([], mw.MW_EINVAL)]:
+        with pytest.raises(mw.MwError) as e:
+            mw.mw_world_create(3, members)
+        assert e.value.code == code
+    with pytest.raises(mw.MwError) as e:
+        mw.mw_world_create(0, [2, 3])
+    assert e.value.code == mw.MW_EEXIST
+    with pytest.raises(mw.MwError) as e:
+        mw.mw_allreduce_sum(0, 0, 0x11, 4, mw.MW_F32)  # not aligned to the element size
+    assert e.value.code == mw.MW_EINVAL
+    assert mw.mw_poll(12345) == mw.MW_EBADHANDLE and mw.mw_poll((77 << 32) | 3) == mw.MW_EBADHANDLE
+    with pytest.raises(mw.MwError) as e:
+        mw.mw_world_state(42)
+    assert e.value.code == mw.MW_ENOWORLD
+
+
+def test_collectives_sequence_and_descriptor_order(ctx):
+    mw.mw_world_create(0, [0, 1, 2])
+    # rank 2 runs ahead by two collectives
+    h = [mw.mw_allreduce_sum(0, 2, 0x300, 16, mw.MW_F32), mw.mw_broadcast(0, 2, 1, 0x310, 8, mw.MW_BF16)]
+    h += [mw.mw_allreduce_sum(0, 0, 0x100, 16, mw.MW_F32), mw.mw_allreduce_sum(0, 1, 0x200, 16, mw.MW_F32)]
+    mw.mw_flush()
+    assert ctx.mwt_log_size() == 1
+    e = log_entry(ctx, 0)
+    assert (e["kind"], e["nbuf"], e["buf"][:3], e["nbytes"]) == (2, 3, [0x100, 0x200, 0x300], 64)
+    h += [mw.mw_broadcast(0, 0, 1, 0x110, 8, mw.MW_BF16), mw.mw_broadcast(0, 1, 1, 0x210, 8, mw.MW_BF16)]
+    mw.mw_flush()
+    e = log_entry(ctx, 1)
+    assert (e["kind"], e["nbuf"], e["buf"][:3], e["nbytes"]) == (1, 3, [0x210, 0x110, 0x310], 16)  # root first
+    ctx.mwt_complete(2, 0)
+    assert [mw.mw_poll(x) for x in h] == [mw.MW_DONE] * 6
+    # disagreement on the root
+    a = mw.mw_broadcast(0, 0, 0, 0x110, 8, mw.MW_BF16)
+    b = mw.mw_broadcast(0, 1, 1, 0x210, 8, mw.MW_BF16)
+    c = mw.mw_broadcast(0, 2, 0, 0x310, 8, mw.MW_BF16)
+    assert [mw.mw_poll(x) for x in (a, b, c)] == [mw.MW_EMISMATCH] * 3
+
+
+def test_abort_breaks_unmatched_delivers_matched_and_refuses_later_posts(ctx):
+    mw.mw_world_create(0, [0, 1])
+    mw.mw_world_create(1, [0, 2])
+    matched_s = mw.mw_send(0, 1, 0, 0x10, 4, mw.MW_F32)
+    matched_r = mw.mw_recv(0, 1, 0, 0x20, 4, mw.MW_F32)  # all sides present, not launched yet
+    lonely = mw.mw_recv(0, 1, 0, 0x30, 4, mw.MW_F32)
+    coll = mw.mw_allreduce_sum(0, 0, 0x40, 4, mw.MW_F32)
+    other = mw.mw_recv(1, 1, 0, 0x50, 4, mw.MW_F32)
+    marks = ctx.mwt_marks()
+    mw.mw_world_abort(0)
+    mw.mw_world_abort(0)  # idempotent
+    assert ctx.mwt_marks() == marks + 1  # one header write: broken + bumped epoch
+    assert mw.mw_world_state(0) == mw.MW_BROKEN and mw.mw_world_state(1) == mw.MW_ALIVE
+    assert mw.mw_poll(lonely) == mw.MW_BROKEN and mw.mw_poll(coll) == mw.MW_BROKEN
+    assert mw.mw_poll(other) == mw.MW_PENDING
+    assert ctx.mwt_launch_count() == 1  # the matched pair was launched by the abort so that it retires
+    assert mw.mw_poll(matched_r) == mw.MW_PENDING
+    ctx.mwt_complete(1, 0)
+    assert mw.mw_poll(matched_s) == mw.MW_DONE and mw.mw_poll(matched_r) == mw.MW_DONE
+    for f in (lambda: mw.mw_send(0, 1, 0, 0x10, 4, mw.MW_F32), lambda: mw.mw_allreduce_sum(0, 1, 0x40, 4, mw.MW_F32)):
+        with pytest.raises(mw.MwError) as e:
+            f()
+        assert e.value.code == mw.MW_EBROKEN
+    hs = mw.mw_send(1, 1, 0, 0x60, 4, mw.MW_F32)
+    mw.mw_flush()
+    ctx.mwt_complete(1, 0)
+    assert mw.mw_poll(hs) == mw.MW_DONE and mw.mw_poll(other) == mw.MW_DONE
+
+
+def test_worker_abort_breaks_exactly_the_worlds_containing_it(ctx):
+    worlds = {10: [0, 1], 11: [0, 2], 12: [1, 3], 13: [2, 3], 14: [4, 5, 6]}
+    for w, m in worlds.items():
+        mw.mw_world_create(w, m)
+    mw.mw_worker_abort(2)
+    assert {w for w in worlds if mw.mw_world_state(w) == mw.MW_BROKEN} == {11, 13}
+    mw.mw_worker_abort(7)  # member of nothing
+    assert {w for w in worlds if mw.mw_world_state(w) == mw.MW_BROKEN} == {11, 13}
+
+
+def test_ring_slots_recycle_and_full_ring_defers(hostlib):
+    mw.mw_config_set("ring_depth", 4)
+    try:
+        mw.mw_init(0, 4)
+        mw.mw_world_create(0, [0, 1])
+        mw.mw_world_create(1, [2, 3])
+        hs = []
+        for k in range(6):
+            mw.mw_send(0, 0, 1, 0x1000 + k, 1, mw.MW_F32)
+            hs.append(mw.mw_recv(0, 0, 1, 0x2000 + k, 1, mw.MW_F32))
+        mw.mw_flush()
+        assert hostlib.mwt_launch_size(0) == 4 and mw.mw_pending_ops() == 6  # two wait for a slot
+        slots = {log_entry(hostlib, i)["slot"] for i in range(4)}
+        assert len(slots) == 4
+        # the other world is not held up by the full ring
+        mw.mw_send(1, 0, 1, 0x3000, 1, mw.MW_F32)
+        ho = mw.mw_recv(1, 0, 1, 0x4000, 1, mw.MW_F32)
+        mw.mw_flush()
+        assert hostlib.mwt_launch_size(1) == 1 and log_entry(hostlib, 4)["world"] == 1
+        hostlib.mwt_complete(2, 0)
+        assert mw.mw_poll(hs[5]) == mw.MW_PENDING  # polling a deferred op retires finished ones and launches it
+        assert hostlib.mwt_launch_count() == 3 and hostlib.mwt_launch_size(2) == 2
+        reused = [log_entry(hostlib, i) for i in (5, 6)]
+        assert {e["slot"] for e in reused} <= slots and all(e["gen"] == 2 for e in reused)
+        hostlib.mwt_complete(10, 0)
+        assert [mw.mw_poll(h) for h in hs] == [mw.MW_DONE] * 6 and mw.mw_poll(ho) == mw.MW_DONE
+    finally:
+        mw.mw_shutdown()
+        mw.mw_config_set("ring_depth", 64)
+
+
+def test_ring_of_a_broken_world_is_reused_only_after_its_operations_retired(hostlib):
+    mw.mw_config_set("max_rings", 2)
+    try:
+        mw.mw_init(0, 6)
+        mw.mw_world_create(0, [0, 1])
+        mw.mw_world_create(1, [2, 3])
+        mw.mw_send(0, 0, 1, 0x10, 1, mw.MW_F32)
+        h = mw.mw_recv(0, 0, 1, 0x20, 1, mw.MW_F32)
+        mw.mw_flush()
+        ring0 = log_entry(hostlib, 0)["slot"] // 64
+        mw.mw_world_abort(0)
+        with pytest.raises(mw.MwError) as e:
+            mw.mw_world_create(2, [4, 5])  # world 0's operation is still in flight: its ring is not free
+        assert e.value.code == mw.MW_ENOMEM
+        hostlib.mwt_complete(1, 0)
+        mw.mw_world_create(2, [4, 5])  # retires world 0's operation, takes over its ring
+        assert mw.mw_poll(h) == mw.MW_DONE
+        mw.mw_send(2, 0, 1, 0x30, 1, mw.MW_F32)
+        mw.mw_recv(2, 0, 1, 0x40, 1, mw.MW_F32)
+        mw.mw_flush()
+        e2 = log_entry(hostlib, 1)
+        assert e2["slot"] // 64 == ring0 and e2["gen"] >= 1 and e2["world"] == 2
+        with pytest.raises(mw.MwError) as e:
+            mw.mw_world_create(0, [0, 1])  # ids are never reused
+        assert e.value.code == mw.MW_EEXIST
+    finally:
+        mw.mw_shutdown()
+        mw.mw_config_set("max_rings", 1024)
+
+
+def test_handles_are_recycled_only_when_terminal(hostlib):
+    mw.mw_config_set("handle_capacity", 16)
+    try:
+        mw.mw_init(0, 2)
+        mw.mw_world_create(0, [0, 1])
+        stuck = mw.mw_recv(0, 1, 0, 0x10, 1, mw.MW_F32)  # never matched: must survive any number of posts
+        first = None
+        for k in range(100):
+            hs = mw.mw_send(0, 0, 1, 0x20, 0, mw.MW_F32)
+            hr = mw.mw_recv(0, 0, 1, 0x30, 0, mw.MW_F32)
+            first = first or hs
+            assert mw.mw_poll(hs) == mw.MW_DONE and mw.mw_poll(hr) == mw.MW_DONE
+        assert mw.mw_poll(stuck) == mw.MW_PENDING
+        assert mw.mw_poll(first) == mw.MW_EBADHANDLE  # its slot has a newer generation now
+        pend = [mw.mw_recv(0, 1, 0, 0x10, 1, mw.MW_F32) for _ in range(15)]
+        with pytest.raises(mw.MwError) as e:
+            mw.mw_recv(0, 1, 0, 0x10, 1, mw.MW_F32)
+        assert e.value.code == mw.MW_ENOMEM  # every slot holds a live operation
+        assert all(mw.mw_poll(h) == mw.MW_PENDING for h in pend)
+    finally:
+        mw.mw_shutdown()
+        mw.mw_config_set("handle_capacity", 1 << 20)
+
+
+def test_launch_failure_is_reported_and_nothing_is_lost(ctx):
+    mw.mw_world_create(0, [0, 1])
+    mw.mw_send(0, 0, 1, 0x10, 1, mw.MW_F32)
+    h = mw.mw_recv(0, 0, 1, 0x20, 1, mw.MW_F32)
+    ctx.mwt_fail_next_launch()
+    with pytest.raises(mw.MwError) as e:
+        mw.mw_flush()
+    assert e.value.code == mw.MW_EHIP and mw.mw_pending_ops() == 1
+    mw.mw_flush()
+    ctx.mwt_complete(1, 0)
+    assert mw.mw_poll(h) == mw.MW_DONE
+
+
+def test_streams_are_deduplicated_and_none_is_skipped(ctx):
+    mw.mw_world_create(0, [0, 1])
+    mw.mw_world_create(1, [2, 3])
+    mw.mw_send(0, 0, 1, 0x10, 1, mw.MW_F32, stream=0x111)
+    mw.mw_recv(0, 0, 1, 0x20, 1, mw.MW_F32, stream=0x111)
+    mw.mw_send(1, 0, 1, 0x30, 1, mw.MW_F32, stream=0x222)
+    mw.mw_recv(1, 0, 1, 0x40, 1, mw.MW_F32, stream=mw.STREAM_NONE)
+    mw.mw_flush()
+    assert ctx.mwt_launch_streams(0) == 2
+    ctx.mwt_complete(2, 0)
+
+
+def test_many_worlds_lookup_is_by_key(ctx):
+    # world ids are arbitrary integers; state is found by key, never by scanning or swapping
+    ids = [7, -3, 1 << 30, 123456, 0]
+    for i, w in enumerate(ids):
+        mw.mw_world_create(w, [i, (i + 1) % 8])
+    hs = []
+    for w in ids:
+        mw.mw_send(w, 0, 1, 0x100, 2, mw.MW_F32)
+        hs.append(mw.mw_recv(w, 0, 1, 0x200, 2, mw.MW_F32))
+    mw.mw_flush()
+    assert ctx.mwt_launch_size(0) == 5 and sorted(log_entry(ctx, i)["world"] for i in range(5)) == sorted(
+        w & 0xFFFFFFFF for w in ids)
+    ctx.mwt_complete(5, 1)  # completion order is irrelevant
+    assert [mw.mw_poll(h) for h in hs] == [mw.MW_DONE] * 5
