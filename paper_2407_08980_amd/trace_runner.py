@@ -83,8 +83,12 @@ def wait_all(outstanding, status, timeout_s=120.0):
             raise TimeoutError(f"{mw.mw_pending_ops()} operations did not complete within {timeout_s} s")
 
 
-def run_trace(trace, host_pools, materialize, device=0, snapshots=True):
-    """Execute `trace`; returns a GpuRun.  mw_init / mw_shutdown bracket the run."""
+def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn=None):
+    """Execute `trace`; returns a GpuRun.  mw_init / mw_shutdown bracket the run.
+
+    check_fn(idx, op, bufs), if given, is called at every "check" op with the dict of live device
+    tensors (buffer id -> uint8 tensor) once everything outstanding has completed; use it with
+    snapshots=False to verify large buffers on the device instead of copying them out."""
     dev = torch.device("cuda", device)
     torch.cuda.set_device(dev)
     pools = DevicePools(host_pools, dev)
@@ -145,6 +149,9 @@ def run_trace(trace, host_pools, materialize, device=0, snapshots=True):
                 wait_all(outstanding, out.status)
                 if snapshots:
                     out.snapshots[idx] = get(op.buf).cpu().numpy().copy()
+                if check_fn is not None:
+                    get(op.buf)
+                    check_fn(idx, op, bufs)
             elif k == "restore":
                 wait_all(outstanding, out.status)
                 if op.buf in bufs:

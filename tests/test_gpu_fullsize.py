@@ -1,0 +1,134 @@
+"""The workloads at their full sizes on the GPU, in the launch configuration bench.py times.
+
+The oracle cannot hold these runs in host memory, so: terminal statuses are compared for every
+operation (the oracle runs the whole trace without data), received == sent is checked on the
+device for every checked message, and seeded byte windows of those messages are compared with
+what the oracle computes from the input recipe.
+"""
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+import workloads
+from oracle.run_trace import run_trace as run_oracle
+from workloads import materialize
+from workloads.data import ITEMSIZE, pool_slice
+
+from helpers import compare_runs
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2407_08980_amd import binding, trace_runner
+
+    binding.lib()
+    return trace_runner
+
+
+def window_of(spec, pools, lo, n):
+    """Bytes [lo, lo+n) of a buffer's initial contents, from its recipe."""
+    kind = spec.init[0]
+    if kind == "fill":
+        return np.full(n, spec.init[1], np.uint8)
+    assert kind == "pool" and lo % ITEMSIZE[spec.init[1]] == 0
+    return pool_slice(pools.get(spec.init[1]), spec.init[1], spec.init[2] + lo // ITEMSIZE[spec.init[1]], n)
+
+
+def windows(nbytes, rng, k=6, width=1 << 16):
+    los = [0, max(0, nbytes - width)] + [int(x) & ~1 for x in rng.integers(0, max(1, nbytes - width), size=k)]
+    return [(lo, min(width, nbytes - lo)) for lo in los]
+
+
+def test_config2_full_size(gpu, host_pools):
+    """8 worlds x 512 MiB bf16, 50 steps; data checked on steps 0-2, 24, 25, 47-49."""
+    import torch
+
+    steps = 50
+    checked = [0, 1, 2, 24, 25, 47, 48, 49]
+    t = workloads.config2(steps=steps, check_steps=checked)
+    rng = np.random.default_rng(2)
+    n_checked = [0]
+
+    def check(idx, op, bufs):
+        # which source fed this destination: step s of world i used src[i][s % 4], dst[i][s % 2]
+        world, slot = divmod(op.buf - 8 * 4, 2)
+        s = checked[n_checked[0] // 8]
+        n_checked[0] += 1
+        src_id = world * 4 + s % 4
+        assert s % 2 == slot
+        assert torch.equal(bufs[op.buf], bufs[src_id]), f"world {world} step {s}: received != sent"
+        for lo, n in windows(t.bufs[op.buf].nbytes, rng):
+            want = oracle.copy_result(window_of(t.bufs[src_id], host_pools, lo, n))
+            assert np.array_equal(bufs[op.buf][lo:lo + n].cpu().numpy(), want), (world, s, lo)
+
+    grun = gpu.run_trace(t, host_pools, lambda sp: materialize(sp, host_pools), snapshots=False, check_fn=check)
+    orun = run_oracle(t, None, data_bufs=set())
+    compare_runs(t, orun, grun, require_checks=False)
+    assert n_checked[0] == 8 * len(checked)
+    assert all(v == "done" for v in grun.status.values()) and len(grun.status) == steps * 16
+    assert grun.payload_bytes_done == steps * 8 * (512 << 20)
+
+
+def test_config4_full_size_fault_isolation(gpu, host_pools):
+    """16 worlds x 160 MiB bf16, 300 steps, worker 7 aborted before step 100."""
+    import torch
+
+    steps, abort_step = 300, 100
+    checked = [0, 1, 98, 99, 100, 101, 102, 298, 299]
+    t = workloads.config4(steps=steps, abort_step=abort_step, check_steps=checked)
+    rng = np.random.default_rng(4)
+    n_checked = [0]
+
+    def check(idx, op, bufs):
+        world, slot = divmod(op.buf - 16 * 4, 2)
+        s = checked[n_checked[0] // 16]
+        n_checked[0] += 1
+        if world == 7 and s >= abort_step:
+            assert bool((bufs[op.buf] == 0xA5).all()), f"step {s}: the broken world's destination was written"
+            return
+        src_id = world * 4 + s % 4
+        assert torch.equal(bufs[op.buf], bufs[src_id]), f"world {world} step {s}: received != sent"
+        for lo, n in windows(t.bufs[op.buf].nbytes, rng, k=2):
+            want = oracle.copy_result(window_of(t.bufs[src_id], host_pools, lo, n))
+            assert np.array_equal(bufs[op.buf][lo:lo + n].cpu().numpy(), want), (world, s, lo)
+
+    grun = gpu.run_trace(t, host_pools, lambda sp: materialize(sp, host_pools), snapshots=False, check_fn=check)
+    orun = run_oracle(t, None, data_bufs=set())
+    compare_runs(t, orun, grun, require_checks=False)
+    assert n_checked[0] == 16 * len(checked)
+    st = list(grun.status.values())
+    assert st.count("done") == 2 * (15 * steps + abort_step) and st.count("broken") == 2 * (steps - abort_step)
+    assert grun.world_state == orun.world_state and [w for w, s in grun.world_state.items() if s == "broken"] == [7]
+    assert grun.payload_bytes_done == (15 * steps + abort_step) * (160 << 20)
+
+
+def test_config3_full_length(gpu, host_pools):
+    """4 worlds x 4 ranks, 500 iterations of two all-reduces; data checked on 12 iterations."""
+    checked = [0, 1, 2, 3, 4, 5, 250, 251, 496, 497, 498, 499]
+    t = workloads.config3(iters=500, check_iters=checked)
+    mat = lambda sp: materialize(sp, host_pools)
+    grun = gpu.run_trace(t, host_pools, mat)
+    orun = run_oracle(t, mat)
+    rep = compare_runs(t, orun, grun)
+    assert rep["toleranced"] == len(checked) * 32 and rep["worst_allreduce_ratio"] <= 3 * 2.0 ** -24
+    assert all(v == "done" for v in grun.status.values()) and len(grun.status) == 500 * 32
+
+
+def test_config5_full_size(gpu, host_pools):
+    """64 worlds, 10 000 mixed operations up to 64 MiB, three worker aborts: every status, and the
+    data of every operation up to 256 KiB plus 1 % of the larger ones."""
+    t = workloads.config5(check_small=1 << 18, check_fraction=0.01)
+    mat = lambda sp: materialize(sp, host_pools)
+    grun = gpu.run_trace(t, host_pools, mat)
+    orun = run_oracle(t, mat)
+    rep = compare_runs(t, orun, grun)
+    assert len(grun.status) == len(orun.status) > 20000
+    assert rep["exact"] > 5000 and rep["toleranced"] > 300
+    assert grun.world_state == orun.world_state
+    assert grun.payload_bytes_done == orun.payload_bytes_done
