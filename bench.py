@@ -37,6 +37,15 @@ def parse():
     ap.add_argument("--reps", type=int, default=5, help="repetitions of the multi-/single-world comparison")
     ap.add_argument("--cpu-steps", type=int, default=6, help="steps of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", type=int, default=0,
+                    help="also run this many plain 1 GiB device copies (torch copy_) before the timed region: the "
+                         "known-size kernel that hardware counters of a profiling run are scaled by")
+    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "config5"], default="config2",
+                    help="config2 (default) is the headline workload; the others are measured the same way")
+    ap.add_argument("--abort-step", type=int, default=100, help="config4: step before which worker 7 is aborted")
+    ap.add_argument("--ops", type=int, default=10_000, help="config5: operations in the trace")
+    ap.add_argument("--chunk-bytes", type=int, default=0, help="pin the kernels' chunk size (0 = chosen per launch)")
+    ap.add_argument("--reduce-lds", type=int, default=0, help="config3: 1 = LDS-staged all-reduce kernel")
     ap.add_argument("--shape", type=int, nargs=3, default=list(SHAPE), help=argparse.SUPPRESS)
     return ap.parse_args()
 
@@ -145,23 +154,8 @@ def cpu_baseline(shape, steps):
     return steps * N_WORLDS * nbytes / dt / 1e9, dt
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print(f"bench.py measures ONE GPU: logical workers share a single device and there is no inter-GPU path "
-              f"(got --gpus {args.gpus})", file=sys.stderr)
-        sys.exit(2)
-    import torch
-
-    if not torch.cuda.is_available():
-        print("bench.py needs the MI355X (no CPU fallback exists)", file=sys.stderr)
-        sys.exit(2)
-    from paper_2407_08980_amd import binding as mw
-
-    mw.lib()
+def main_config2(args, torch, mw, dev):
     shape = tuple(args.shape)
-    dev = torch.device("cuda", 0)
-    torch.cuda.set_device(dev)
     mw.mw_init(0, 2 * N_WORLDS)
     wl = Workload(torch, mw, shape, dev)
     # multi-world: world w = (worker 2w -> worker 2w+1); single world: one world of all 16 workers
@@ -172,6 +166,13 @@ def main():
     multi = (list(range(N_WORLDS)), [(0, 1)] * N_WORLDS)
     single = ([SINGLE] * N_WORLDS, [(2 * w, 2 * w + 1) for w in range(N_WORLDS)])
 
+    if args.calibrate:
+        a = torch.full((1 << 30,), 3, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(args.calibrate):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     K, W = args.steps, args.warmup
     wl.run(W, *multi)
     mw.mw_profile_enable(True)
@@ -188,7 +189,8 @@ def main():
     for r in range(args.reps):
         sw_rates.append(K * step_payload / wl.timed(K, *single) / 1e9)
         mw_rates.append(K * step_payload / wl.timed(K, *multi) / 1e9)
-    wl.verify_last(K)
+    if args.reps:
+        wl.verify_last(K)
     mean = lambda v: sum(v) / len(v) if v else float("nan")
     loss_pct = (1.0 - mean(mw_rates) / mean(sw_rates)) * 100.0 if args.reps else None
 
@@ -250,6 +252,418 @@ def main():
                       f"({args.cpu_steps * N_WORLDS} messages of {shape[0] * shape[1] * shape[2] * 2 >> 20} MiB), "
                       f"{secs:.1f} s of oracle time; host has {os.cpu_count()} logical CPUs",
         }
+    print(json.dumps(out))
+
+
+
+# --------------------------------------------------------------------------------------------------
+# the other workloads (timing only; their parity is covered by tests/)
+# --------------------------------------------------------------------------------------------------
+def _profile(mw, kind):
+    launches, ms, op_bytes = mw.mw_profile_read(kind)
+    return launches, ms, op_bytes
+
+
+def run_config4(torch, mw, dev, steps, abort_step, reps):
+    """Elastic fan-in: 16 producers -> one shared consumer, 160 MiB bf16 messages, producer 7 aborted
+    before step `abort_step`; its world keeps being attempted (and refused) afterwards."""
+    from paper_2407_08980_amd.trace_runner import DevicePools
+    from workloads import HostPools
+    from workloads.data import POOL_ELEMS, rng_of
+
+    n, count = 16, 8 * 2048 * 5120
+    nbytes = count * 2
+    pools = DevicePools(HostPools(), dev)
+    rng = rng_of(20240708 + 4)
+    src = []
+    for w in range(n):
+        row = []
+        for k in range(POOL_K):
+            t = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            pools.slice("bf16", int(rng.integers(0, POOL_ELEMS)), nbytes, t)
+            row.append(t)
+        src.append(row)
+    dst = [[torch.full((nbytes,), 0xA5, dtype=torch.uint8, device=dev) for _ in range(2)] for _ in range(n)]
+    streams = [torch.cuda.Stream(device=dev) for _ in range(n)]
+    torch.cuda.synchronize()
+
+    def batches(world_of, ranks_of):
+        out = []
+        for s in range(4):  # period of (s % POOL_K, s % 2)
+            posts = []
+            for w in range(n):
+                a, b = ranks_of[w]
+                st = streams[w].cuda_stream
+                posts.append((mw.POST_SEND, world_of[w], a, b, src[w][s % POOL_K].data_ptr(), count, mw.MW_BF16, st))
+                posts.append((mw.POST_RECV, world_of[w], a, b, dst[w][s % 2].data_ptr(), count, mw.MW_BF16, st))
+            out.append(mw.PostBatch(posts))
+        return out
+
+    def run(base_world, single, abort_at):
+        """One pass of `steps` steps; returns (seconds, done messages, per-step completion stamps)."""
+        if single:
+            mw.mw_world_create(base_world, list(range(n + 1)))
+            world_of, ranks_of = [base_world] * n, [(w, n) for w in range(n)]
+        else:
+            for w in range(n):
+                mw.mw_world_create(base_world + w, [w, n])
+            world_of, ranks_of = [base_world + w for w in range(n)], [(0, 1)] * n
+        pbs = batches(world_of, ranks_of)
+        stamps, done = [], 0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        prev = None
+        for s in range(steps):
+            if abort_at is not None and s == abort_at:
+                mw.mw_worker_abort(7)
+            pb = pbs[s % 4]
+            pb.post(check=False)
+            mw.mw_flush()
+            cur = mw.PollSet([h for h in pb.handles if h])
+            if prev is not None:
+                _poll_until_idle_set(prev)
+                stamps.append(time.perf_counter() - t0)
+                done += sum(1 for x in prev.states if x == mw.MW_DONE) // 2
+            prev = cur
+        _poll_until_idle_set(prev)
+        stamps.append(time.perf_counter() - t0)
+        done += sum(1 for x in prev.states if x == mw.MW_DONE) // 2
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, done, stamps
+
+    def _poll_until_idle_set(ps):
+        if ps.n == 0:
+            return
+        while ps.poll():
+            pass
+
+    base = [100]
+
+    def fresh():
+        base[0] += 100
+        return base[0]
+
+    run(fresh(), False, None)  # warm-up
+    mw.mw_profile_enable(True)
+    mw.mw_profile_read(mw.KIND_COPY)
+    secs, done, stamps = run(fresh(), False, abort_step)
+    launches, kernel_ms, op_bytes = _profile(mw, mw.KIND_COPY)
+    mw.mw_profile_enable(False)
+    for w in range(n):  # the healthy worlds' last messages arrived; the broken world's destination kept step 99's data
+        s_last = steps - 1 if w != 7 else abort_step - 1
+        if not torch.equal(dst[w][s_last % 2], src[w][s_last % POOL_K]):
+            raise RuntimeError(f"world {w}: destination differs from source")
+    value = done * nbytes / secs / 1e9
+    mw_r, sw_r = [], []
+    for _ in range(reps):
+        t, d, _ = run(fresh(), True, None)
+        sw_r.append(d * nbytes / t / 1e9)
+        t, d, _ = run(fresh(), False, None)
+        mw_r.append(d * nbytes / t / 1e9)
+    t_sw_abort, d_sw_abort, _ = run(fresh(), True, abort_step)
+    mean = lambda v: sum(v) / len(v) if v else float("nan")
+    step_ms = [round((stamps[i] - stamps[i - 1]) * 1e3, 3) for i in range(max(1, abort_step - 5), min(steps, abort_step + 6))]
+    avg_ms = kernel_ms / max(launches, 1)
+    achieved = 2.0 * op_bytes / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
+    return {
+        "value": round(value, 1), "ms_per_step": round(secs / steps * 1e3, 4), "steps": steps,
+        "config": {"workload": f"config 4: elastic fan-in with a fault, 16 worlds (producer i -> shared consumer), bf16 "
+                               f"[8, 2048, 5120] = {nbytes >> 20} MiB per message, worker 7 aborted before step {abort_step} "
+                               f"of {steps}", "worlds": n, "payload_dtype": "bf16", "steps_in_flight": 2},
+        "messages_done": done, "messages_expected_done": 15 * steps + min(abort_step, steps),
+        "hbm_traffic_GBps": round(2 * value, 1), "pct_of_hbm_peak": round(2 * value / HBM_PEAK_GBPS * 100, 2),
+        "step_ms_around_abort": step_ms,
+        "single_world_GBps": round(mean(sw_r), 1) if reps else None,
+        "multi_world_GBps_mean": round(mean(mw_r), 1) if reps else None,
+        "loss_vs_single_world_pct": round((1 - mean(mw_r) / mean(sw_r)) * 100, 3) if reps else None,
+        "single_world_with_abort_messages_done": d_sw_abort,
+        "roofline": {"bound": "hbm", "kernel": "mw_k_copy", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "launches": launches, "avg_launch_ms": round(avg_ms, 4)},
+    }
+
+
+def run_config3(torch, mw, dev, iters, reps, lds):
+    """Tensor-parallel partial sums: 4 worlds x 4 ranks, all-reduce of fp32 [16,4096] and [16,14336] per
+    iteration, all worlds outstanding together.  Latency-bound and cache-resident (28 MiB working set)."""
+    mw.mw_config_set("reduce_lds", lds)
+    n_worlds, n_ranks = 4, 4
+    counts = [16 * 4096, 16 * 14336]
+    g = torch.Generator(device=dev)
+    g.manual_seed(20240708 + 3)
+    bufs = [[[[torch.rand(c, dtype=torch.float32, device=dev, generator=g) * 2 - 1 for c in counts]
+              for _ in range(POOL_K)] for _ in range(n_ranks)] for _ in range(n_worlds)]
+    torch.cuda.synchronize()
+    per_iter_bytes = n_worlds * sum(counts) * 4  # payload S summed over the collectives of one iteration
+
+    def make(world_of):
+        out = []
+        for k in range(POOL_K):
+            posts = []
+            for j, c in enumerate(counts):
+                for w in range(n_worlds):
+                    for r in range(n_ranks):
+                        posts.append((mw.POST_ALLREDUCE_SUM, world_of[w], r, 0, bufs[w][r][k][j].data_ptr(), c, mw.MW_F32,
+                                      mw.STREAM_NONE))
+            out.append(mw.PostBatch(posts))
+        return out
+
+    def run(pbs, n_iter):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        prev = None
+        for it in range(n_iter):
+            pb = pbs[it % POOL_K]
+            pb.post()
+            mw.mw_flush()
+            cur = mw.PollSet(list(pb.handles))
+            if prev is not None:
+                while prev.poll():
+                    pass
+            prev = cur
+        while prev.poll():
+            pass
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    for w in range(n_worlds):
+        mw.mw_world_create(w, list(range(w * n_ranks, (w + 1) * n_ranks)))
+    mw.mw_world_create(99, [0, 1, 2, 3])
+    multi, single = make(list(range(n_worlds))), make([99] * n_worlds)
+    run(multi, 20)
+    mw.mw_profile_enable(True)
+    mw.mw_profile_read(mw.KIND_REDUCE)
+    secs = run(multi, iters)
+    launches, kernel_ms, op_bytes = _profile(mw, mw.KIND_REDUCE)
+    mw.mw_profile_enable(False)
+    mw_r, sw_r = [], []
+    for _ in range(reps):
+        sw_r.append(iters * per_iter_bytes / run(single, iters) / 1e9)
+        mw_r.append(iters * per_iter_bytes / run(multi, iters) / 1e9)
+    mean = lambda v: sum(v) / len(v) if v else float("nan")
+    value = iters * per_iter_bytes / secs / 1e9
+    alg = 2.0 * n_ranks * op_bytes  # n reads + n writes of every payload
+    achieved = alg / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
+    return {
+        "value": round(value, 2), "ms_per_step": round(secs / iters * 1e3, 4), "steps": iters,
+        "config": {"workload": "config 3: tensor-parallel partial-sum all-reduce, 4 worlds x 4 ranks, fp32 [16,4096] + "
+                               "[16,14336] per iteration, all worlds concurrent (latency-bound, cache-resident)",
+                   "worlds": n_worlds, "ranks": n_ranks, "payload_dtype": "f32", "steps_in_flight": 2,
+                   "reduce_lds": lds},
+        "us_per_iteration": round(secs / iters * 1e6, 2),
+        "algorithmic_traffic_GBps": round(2 * n_ranks * value, 1),
+        "single_world_GBps": round(mean(sw_r), 2) if reps else None,
+        "multi_world_GBps_mean": round(mean(mw_r), 2) if reps else None,
+        "loss_vs_single_world_pct": round((1 - mean(mw_r) / mean(sw_r)) * 100, 3) if reps else None,
+        "roofline": {"bound": "hbm", "kernel": "mw_k_reduce", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "launches": launches,
+                     "avg_launch_ms": round(kernel_ms / max(launches, 1), 5),
+                     "note": "working set fits the 256 MB last-level cache: not an HBM figure"},
+    }
+
+
+def run_config1(torch, mw, dev, reps):
+    """Two worlds sharing a leader, 200 fp32 [8,1024] messages alternating between them, windows of 16;
+    also the round trip of one message (post -> flush -> first poll that reports done)."""
+    count, n_msgs, window = 8 * 1024, 200, 16
+    src = torch.randn(n_msgs, count, device=dev)
+    dst = torch.zeros(n_msgs, count, device=dev)
+    torch.cuda.synchronize()
+    mw.mw_world_create(0, [0, 1])
+    mw.mw_world_create(1, [0, 2])
+    mw.mw_world_create(2, [0, 1, 2])
+
+    def make(single):
+        out = []
+        for lo in range(0, n_msgs, window):
+            posts = []
+            for k in range(lo, min(lo + window, n_msgs)):
+                w, a = (2, 1 + k % 2) if single else (k % 2, 1)
+                posts.append((mw.POST_SEND, w, a, 0, src[k].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE))
+                posts.append((mw.POST_RECV, w, a, 0, dst[k].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE))
+            out.append(mw.PostBatch(posts))
+        return out
+
+    def run(pbs):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for pb in pbs:
+            pb.post()
+            mw.mw_flush()
+            ps = mw.PollSet(list(pb.handles))
+            while ps.poll():
+                pass
+        return time.perf_counter() - t0
+
+    multi, single = make(False), make(True)
+    for _ in range(5):
+        run(multi), run(single)
+    mw_t, sw_t = [], []
+    for _ in range(max(reps, 1) * 8):  # interleaved so that clock and cache state are shared
+        sw_t.append(run(single))
+        mw_t.append(run(multi))
+    if not torch.equal(src, dst):
+        raise RuntimeError("config 1: destination differs from source")
+    rt = []
+    for k in range(200):
+        t0 = time.perf_counter()
+        hs = mw.mw_send(k % 2, 1, 0, src[k].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE)
+        hr = mw.mw_recv(k % 2, 1, 0, dst[k].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE)
+        mw.mw_flush()
+        while mw.mw_poll(hr) != mw.MW_DONE:
+            pass
+        rt.append(time.perf_counter() - t0)
+    rt.sort()
+    mean = lambda v: sum(v) / len(v)
+    secs = mean(mw_t)
+    value = n_msgs * count * 4 / secs / 1e9
+    return {
+        "value": round(value, 3), "ms_per_step": round(secs * 1e3, 4), "steps": len(mw_t),
+        "config": {"workload": "config 1: 2 worlds over 3 workers (leader in both), 200 fp32 [8,1024] messages "
+                               "alternating between the worlds, windows of 16 (latency-bound)", "worlds": 2,
+                   "payload_dtype": "f32"},
+        "us_per_message_windowed": round(secs / n_msgs * 1e6, 3),
+        "messages_per_s": round(n_msgs / secs),
+        "single_message_round_trip_us": {"median": round(rt[len(rt) // 2] * 1e6, 2), "p10": round(rt[len(rt) // 10] * 1e6, 2),
+                                         "p90": round(rt[9 * len(rt) // 10] * 1e6, 2)},
+        "single_world_GBps": round(n_msgs * count * 4 / mean(sw_t) / 1e9, 3),
+        "loss_vs_single_world_pct": round((1 - mean(sw_t) / mean(mw_t)) * 100, 3),
+        "roofline": None,
+    }
+
+
+def run_config5(torch, mw, dev, n_ops, reps):
+    """Mixed scale-out: the seeded 10 000-operation trace (64 worlds of 2-4 over 32 workers, 70/20/10 %
+    p2p / broadcast / all-reduce, 4 KiB - 64 MiB, fp32/bf16, three worker aborts), <= 64 outstanding.
+    Buffers are slices of one pre-filled slab so that no initialisation runs inside the timed region."""
+    import workloads
+
+    t = workloads.config5(n_ops=n_ops)
+    slab_bytes = 40 << 30
+    slab = torch.empty(slab_bytes, dtype=torch.uint8, device=dev)
+    g = torch.Generator(device=dev)
+    g.manual_seed(5)
+    step = 1 << 30
+    for o in range(0, slab_bytes, step):  # finite fp32/bf16 bit patterns: small integers in every byte pair
+        slab[o:o + step].view(torch.int16).random_(0, 0x3F80, generator=g)
+    torch.cuda.synchronize()
+    base = slab.data_ptr()
+    kind_of = {"send": mw.POST_SEND, "recv": mw.POST_RECV, "bcast": mw.POST_BROADCAST, "allreduce": mw.POST_ALLREDUCE_SUM}
+
+    def segments(world_base):
+        segs, posts, off, where = [], [], 0, {}
+        for op in t.ops:
+            if op.kind in kind_of:
+                if op.buf not in where:
+                    nb = (t.bufs[op.buf].nbytes + 255) & ~255
+                    assert off + nb <= slab_bytes, "slab too small for a window"
+                    where[op.buf] = off
+                    off += nb
+                posts.append((kind_of[op.kind], world_base + op.world, op.a, max(op.b, 0), base + where[op.buf], op.count,
+                              mw.DTYPES[op.dtype], mw.STREAM_NONE))
+            elif op.kind == "abort_worker":
+                if posts:
+                    segs.append(("post", mw.PostBatch(posts)))
+                    posts = []
+                segs.append(("abort", op.a))
+            elif op.kind == "wait":
+                if posts:
+                    segs.append(("post", mw.PostBatch(posts)))
+                    posts = []
+                segs.append(("wait", None))
+                off, where = 0, {}
+        return segs
+
+    def run(world_base):
+        for op in t.ops:
+            if op.kind == "create":
+                mw.mw_world_create(world_base + op.world, list(op.members))
+        segs = segments(world_base)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        live = []
+        for kind, x in segs:
+            if kind == "post":
+                x.post(check=False)
+                live.append(x)
+            elif kind == "abort":
+                mw.mw_worker_abort(x)
+            else:
+                mw.mw_flush()
+                sets = [mw.PollSet([h for h in pb.handles if h]) for pb in live]
+                while mw.mw_pending_ops():
+                    for ps in sets:
+                        if ps.n:
+                            ps.poll()
+                live = []
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    # payload of the operations that complete: everything posted to a world that is still alive
+    dead, payload, alg = set(), 0, 0
+    members = t.meta["members"]
+    for op in t.ops:
+        if op.kind == "abort_worker":
+            dead.add(op.a)
+        elif op.kind in kind_of and not (dead & set(members[op.world])):
+            S = op.count * (4 if op.dtype == "f32" else 2)
+            n = len(members[op.world])
+            if op.kind == "recv":
+                payload += S
+                alg += 2 * S
+            elif op.kind == "bcast" and op.a == 0:
+                payload += S
+                alg += n * S
+            elif op.kind == "allreduce" and op.a == 0:
+                payload += S
+                alg += 2 * n * S
+    run(10_000)  # warm-up (worker aborts only break this pass's worlds)
+    times = [run(10_000 * (i + 2)) for i in range(max(reps, 1))]
+    secs = sum(times) / len(times)
+    return {
+        "value": round(payload / secs / 1e9, 1), "ms_per_step": round(secs * 1e3, 3), "steps": len(times),
+        "config": {"workload": f"config 5: mixed scale-out, 64 worlds of 2-4 over 32 workers, {n_ops} operations 70/20/10 % "
+                               "send-recv / broadcast / all-reduce, 4 KiB - 64 MiB log-uniform, fp32/bf16, 3 worker "
+                               "aborts, <= 64 outstanding", "worlds": 64, "payload_dtype": "f32/bf16"},
+        "payload_bytes_done": payload, "algorithmic_bytes": alg,
+        "hbm_traffic_GBps": round(alg / secs / 1e9, 1), "pct_of_hbm_peak": round(alg / secs / 1e9 / HBM_PEAK_GBPS * 100, 2),
+        "roofline": None,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py measures ONE GPU: logical workers share a single device and there is no inter-GPU path "
+              f"(got --gpus {args.gpus})", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py needs the MI355X (no CPU fallback exists)", file=sys.stderr)
+        sys.exit(2)
+    from paper_2407_08980_amd import binding as mw
+
+    mw.lib()
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+    mw.mw_config_set("chunk_bytes", args.chunk_bytes)
+    if args.workload == "config2":
+        return main_config2(args, torch, mw, dev)
+    mw.mw_init(0, 64)
+    if args.workload == "config4":
+        res = run_config4(torch, mw, dev, args.steps if args.steps != 50 else 300, args.abort_step, args.reps)
+    elif args.workload == "config3":
+        res = run_config3(torch, mw, dev, args.steps if args.steps != 50 else 500, args.reps, args.reduce_lds)
+    elif args.workload == "config1":
+        res = run_config1(torch, mw, dev, args.reps)
+    else:
+        res = run_config5(torch, mw, dev, args.ops, args.reps)
+    mw.mw_shutdown()
+    out = {"metric": METRIC, "value": res.pop("value"), "unit": "GB/s", "n_gpus": 1, "steps": res.pop("steps"),
+           "warmup": args.warmup, "ms_per_step": res.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32" if args.workload == "config3" else "u8", "data": "synthetic"}
+    out.update(res)
     print(json.dumps(out))
 
 

@@ -144,6 +144,26 @@ int mw_poll(mw_handle h);
  * posts batches them into one launch. */
 int mw_flush(void);
 
+/* Post many sides with one call (one lock acquisition): posts[i] is what the corresponding
+ * mw_send / mw_recv / mw_broadcast / mw_allreduce_sum call would take -- `a`/`b` are src/dst rank for
+ * point-to-point, rank/root for broadcast, rank/unused for all-reduce.  Posts are processed in array
+ * order and independently: handles[i] is the handle, or 0 if that post was refused; results[i] (may be
+ * NULL) is its return code.  Returns MW_OK or the first refusal's code.  Host arrays, read/written
+ * during the call. */
+typedef enum { MW_POST_SEND = 0, MW_POST_RECV = 1, MW_POST_BROADCAST = 2, MW_POST_ALLREDUCE_SUM = 3 } mw_post_kind;
+typedef struct {
+  int32_t kind; /* mw_post_kind */
+  int32_t world_id;
+  int32_t a;
+  int32_t b;
+  void* buf;
+  uint64_t count;
+  int32_t dtype; /* mw_dtype */
+  int32_t reserved;
+  void* hip_stream;
+} mw_post_desc;
+int mw_post_many(const mw_post_desc* posts, int n, mw_handle* handles, int* results);
+
 /* Number of operations that have all their sides posted and have not yet been seen complete by a
  * poll (queued for launch or in flight).  0 means every remaining MW_PENDING handle waits for a peer. */
 int mw_pending_ops(void);

@@ -26,10 +26,19 @@ KIND_COPY, KIND_BCAST, KIND_REDUCE = 0, 1, 2
 
 SYMBOLS = [
     "mw_init", "mw_shutdown", "mw_world_create", "mw_world_abort", "mw_worker_abort", "mw_world_state",
-    "mw_send", "mw_recv", "mw_broadcast", "mw_allreduce_sum", "mw_poll", "mw_flush", "mw_pending_ops", "mw_poll_many",
+    "mw_send", "mw_recv", "mw_broadcast", "mw_allreduce_sum", "mw_poll", "mw_flush", "mw_pending_ops", "mw_poll_many", "mw_post_many",
     "mw_config_set", "mw_config_get", "mw_handle_capacity", "mw_last_hip_error", "mw_strerror",
     "mw_profile_enable", "mw_profile_read", "mw_debug_ring_read", "mw_debug_arena_hash",
 ]
+
+
+POST_SEND, POST_RECV, POST_BROADCAST, POST_ALLREDUCE_SUM = 0, 1, 2, 3
+
+
+class PostDesc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("world_id", C.c_int32), ("a", C.c_int32), ("b", C.c_int32),
+                ("buf", C.c_void_p), ("count", C.c_uint64), ("dtype", C.c_int32), ("reserved", C.c_int32),
+                ("hip_stream", C.c_void_p)]
 
 
 class MwError(RuntimeError):
@@ -58,6 +67,7 @@ def declare(lib):
     lib.mw_flush.argtypes = []
     lib.mw_pending_ops.argtypes = []
     lib.mw_poll_many.argtypes = [u64p, i, C.POINTER(C.c_int)]
+    lib.mw_post_many.argtypes = [C.POINTER(PostDesc), i, u64p, C.POINTER(C.c_int)]
     lib.mw_config_set.argtypes = [C.c_char_p, C.c_long]
     lib.mw_config_get.argtypes = [C.c_char_p]
     lib.mw_config_get.restype = C.c_long
@@ -175,6 +185,32 @@ class PollSet:
     def poll(self):
         """Number of handles still pending; self.states holds every state."""
         return _ck(lib().mw_poll_many(self.handles, self.n, self.states), "mw_poll_many")
+
+
+class PostBatch:
+    """A reusable array of posts for mw_post_many: (kind, world, a, b, buf, count, dtype, stream) tuples."""
+
+    def __init__(self, posts):
+        self.n = len(posts)
+        self.descs = (PostDesc * self.n)()
+        for d, (kind, world, a, b, buf, count, dtype, stream) in zip(self.descs, posts):
+            d.kind, d.world_id, d.a, d.b, d.buf, d.count, d.dtype = kind, world, a, b, buf, count, dtype
+            d.hip_stream = stream if stream != STREAM_NONE else C.c_void_p(-1).value
+        self.handles = (C.c_uint64 * self.n)()
+        self.results = (C.c_int * self.n)()
+
+    def post(self, check=True):
+        rc = lib().mw_post_many(self.descs, self.n, self.handles, self.results)
+        if check:
+            _ck(rc, "mw_post_many")
+        return rc
+
+
+def mw_post_many(posts):
+    """Post a list of (kind, world, a, b, buf, count, dtype, stream); returns (handles, results)."""
+    pb = PostBatch(posts)
+    pb.post(check=False)
+    return list(pb.handles), list(pb.results)
 
 
 def mw_poll_many(handles):

@@ -647,8 +647,10 @@ class HipDevice : public Device {
     if (cfg_.chunk_bytes) return floor_log2(cfg_.chunk_bytes);
     // enough workgroups to fill 256 CUs several times over, chunks large enough to amortise
     // the per-chunk completion protocol
+    // Copies peak at 128 KiB chunks (two passes of 1024 threads x 4 x 16 B): measured 6.10 TB/s of
+    // traffic on 8 x 512 MiB against 5.59 (64 KiB), 5.94 (256 KiB), 5.19 (512 KiB), 5.78 (1 MiB).
     const uint32_t lo = kind == kReduce ? 12 : 14;   // 4 KiB / 16 KiB
-    const uint32_t hi = kind == kReduce ? 16 : 18;   // 64 KiB / 256 KiB
+    const uint32_t hi = kind == kReduce ? 16 : 17;   // 64 KiB / 128 KiB
     uint32_t s = floor_log2(total_bytes / 2048 + 1);
     return std::min(hi, std::max(lo, s));
   }

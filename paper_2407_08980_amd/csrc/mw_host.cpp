@@ -283,11 +283,8 @@ int enqueue_op(Context& c, uint32_t wi, uint32_t kind, uint32_t dtype, uint64_t 
 inline uint64_t item_size(uint32_t dtype) { return dtype == MW_F32 ? 4 : 2; }
 
 // ---- posting -----------------------------------------------------------------------------------
-int post_p2p(bool is_send, int world_id, int src, int dst, const void* buf, size_t count, mw_dtype dtype,
-             void* stream, mw_handle* out) {
-  std::lock_guard<std::mutex> g(g_lock);
-  if (!g_ctx) return MW_ENOTINIT;
-  Context& c = *g_ctx;
+int post_p2p_locked(Context& c, bool is_send, int world_id, int src, int dst, const void* buf, size_t count,
+                    mw_dtype dtype, void* stream, mw_handle* out) {
   if (!out || (dtype != MW_F32 && dtype != MW_BF16)) return MW_EINVAL;
   auto it = c.world_of_id.find(world_id);
   if (it == c.world_of_id.end()) return MW_ENOWORLD;
@@ -325,11 +322,8 @@ int post_p2p(bool is_send, int world_id, int src, int dst, const void* buf, size
   return enqueue_op(c, it->second, kCopy, (uint32_t)dtype, count * item_size(dtype), pair, 2, order);
 }
 
-int post_coll(uint32_t kind, int world_id, int rank, int root, void* buf, size_t count, mw_dtype dtype,
-              void* stream, mw_handle* out) {
-  std::lock_guard<std::mutex> g(g_lock);
-  if (!g_ctx) return MW_ENOTINIT;
-  Context& c = *g_ctx;
+int post_coll_locked(Context& c, uint32_t kind, int world_id, int rank, int root, void* buf, size_t count,
+                     mw_dtype dtype, void* stream, mw_handle* out) {
   if (!out || (dtype != MW_F32 && dtype != MW_BF16)) return MW_EINVAL;
   auto it = c.world_of_id.find(world_id);
   if (it == c.world_of_id.end()) return MW_ENOWORLD;
@@ -387,6 +381,20 @@ int post_coll(uint32_t kind, int world_id, int rank, int root, void* buf, size_t
     if (rc != MW_OK) return rc;
   }
   return MW_OK;
+}
+
+int post_p2p(bool is_send, int world_id, int src, int dst, const void* buf, size_t count, mw_dtype dtype,
+             void* stream, mw_handle* out) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  return post_p2p_locked(*g_ctx, is_send, world_id, src, dst, buf, count, dtype, stream, out);
+}
+
+int post_coll(uint32_t kind, int world_id, int rank, int root, void* buf, size_t count, mw_dtype dtype,
+              void* stream, mw_handle* out) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  return post_coll_locked(*g_ctx, kind, world_id, rank, root, buf, count, dtype, stream, out);
 }
 
 int abort_world_locked(Context& c, World& w) {
@@ -567,6 +575,42 @@ int mw_broadcast(int world_id, int rank, int root_rank, void* buf, size_t count,
 int mw_allreduce_sum(int world_id, int rank, void* buf, size_t count, mw_dtype dtype, void* hip_stream,
                      mw_handle* out) {
   return post_coll(kReduce, world_id, rank, 0, buf, count, dtype, hip_stream, out);
+}
+
+int mw_post_many(const mw_post_desc* posts, int n, mw_handle* handles, int* results) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  if (n < 0 || (n > 0 && (!posts || !handles))) return MW_EINVAL;
+  int first_err = MW_OK;
+  for (int i = 0; i < n; ++i) {
+    const mw_post_desc& p = posts[i];
+    handles[i] = 0;
+    int rc;
+    switch (p.kind) {
+      case MW_POST_SEND:
+        rc = post_p2p_locked(*g_ctx, true, p.world_id, p.a, p.b, p.buf, (size_t)p.count, (mw_dtype)p.dtype,
+                             p.hip_stream, &handles[i]);
+        break;
+      case MW_POST_RECV:
+        rc = post_p2p_locked(*g_ctx, false, p.world_id, p.a, p.b, p.buf, (size_t)p.count, (mw_dtype)p.dtype,
+                             p.hip_stream, &handles[i]);
+        break;
+      case MW_POST_BROADCAST:
+        rc = post_coll_locked(*g_ctx, kBcast, p.world_id, p.a, p.b, p.buf, (size_t)p.count, (mw_dtype)p.dtype,
+                              p.hip_stream, &handles[i]);
+        break;
+      case MW_POST_ALLREDUCE_SUM:
+        rc = post_coll_locked(*g_ctx, kReduce, p.world_id, p.a, 0, p.buf, (size_t)p.count, (mw_dtype)p.dtype,
+                              p.hip_stream, &handles[i]);
+        break;
+      default:
+        rc = MW_EINVAL;
+    }
+    if (rc != MW_OK) handles[i] = 0;
+    if (results) results[i] = rc;
+    if (rc != MW_OK && first_err == MW_OK) first_err = rc;
+  }
+  return first_err;
 }
 
 int mw_poll(mw_handle h) {
