@@ -38,8 +38,14 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kCopyWG = 1024;   // threads per workgroup, copy / broadcast
 constexpr int kCopyU = 4;       // 16-byte vectors in flight per thread
-constexpr int kReduceWG = 256;
-constexpr int kReduceU = 2;
+#ifndef MW_REDUCE_WG
+#define MW_REDUCE_WG 1024
+#endif
+#ifndef MW_REDUCE_U
+#define MW_REDUCE_U 1
+#endif
+constexpr int kReduceWG = MW_REDUCE_WG;  // threads per workgroup, all-reduce
+constexpr int kReduceU = MW_REDUCE_U;    // 16-byte vectors per rank in flight per thread
 constexpr int kCopyMax = 80;    // operations per copy launch (kernel arguments stay under 4 KiB)
 constexpr int kCollMax = 36;    // operations per broadcast / all-reduce launch
 
@@ -649,8 +655,10 @@ class HipDevice : public Device {
     // the per-chunk completion protocol
     // Copies peak at 128 KiB chunks (two passes of 1024 threads x 4 x 16 B): measured 6.10 TB/s of
     // traffic on 8 x 512 MiB against 5.59 (64 KiB), 5.94 (256 KiB), 5.19 (512 KiB), 5.78 (1 MiB).
-    const uint32_t lo = kind == kReduce ? 12 : 14;   // 4 KiB / 16 KiB
-    const uint32_t hi = kind == kReduce ? 16 : 17;   // 64 KiB / 128 KiB
+    // All-reduce peaks at 16 KiB per rank (one pass of 1024 threads x 16 B over every rank):
+    // 5.73 TB/s on 8 x (4 ranks x 64 MiB) against 5.29 (8 KiB / 32 KiB) and 4.77 (64 KiB).
+    const uint32_t lo = kind == kReduce ? 13 : 14;   // 8 KiB / 16 KiB
+    const uint32_t hi = kind == kReduce ? 14 : 17;   // 16 KiB / 128 KiB
     uint32_t s = floor_log2(total_bytes / 2048 + 1);
     return std::min(hi, std::max(lo, s));
   }
