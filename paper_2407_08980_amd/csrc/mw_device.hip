@@ -499,7 +499,8 @@ class HipDevice : public Device {
       return MW_EHIP;
     std::memset(flags_host_, 0, (size_t)cfg.total_slots * sizeof(uint32_t));
     if (chk(hipHostGetDevicePointer(reinterpret_cast<void**>(&flags_dev_), flags_host_, 0))) return MW_EHIP;
-    if (chk(hipStreamCreateWithFlags(&data_, hipStreamNonBlocking))) return MW_EHIP;
+    for (auto& st : data_)
+      if (chk(hipStreamCreateWithFlags(&st, hipStreamNonBlocking))) return MW_EHIP;
     if (chk(hipStreamCreateWithFlags(&ctl_, hipStreamNonBlocking))) return MW_EHIP;
     dep_events_.resize(kDepEvents);
     for (auto& e : dep_events_)
@@ -512,7 +513,7 @@ class HipDevice : public Device {
   void shutdown() override {
     if (!ready_) return;
     (void)hipSetDevice(dev_);
-    (void)hipStreamSynchronize(data_);
+    for (auto& st : data_) (void)hipStreamSynchronize(st);
     (void)hipStreamSynchronize(ctl_);
     for (auto& e : dep_events_) (void)hipEventDestroy(e);
     for (auto& r : prof_) {
@@ -520,7 +521,7 @@ class HipDevice : public Device {
       (void)hipEventDestroy(r.stop);
     }
     for (auto& e : prof_free_) (void)hipEventDestroy(e);
-    (void)hipStreamDestroy(data_);
+    for (auto& st : data_) (void)hipStreamDestroy(st);
     (void)hipStreamDestroy(ctl_);
     (void)hipFree(arena_);
     (void)hipHostFree(flags_host_);
@@ -534,7 +535,10 @@ class HipDevice : public Device {
 
   int launch(const LaunchOp* ops, int n, void* const* streams, int n_streams) override {
     if (chk(hipSetDevice(dev_))) return MW_EHIP;
-    // order after the callers' streams
+    // Each kernel kind has its own stream so that a copy, a broadcast and an all-reduce launch of one
+    // flush overlap.  Order every stream used by this flush after the callers' busy streams.
+    bool used[kNumKinds] = {};
+    for (int i = 0; i < n; ++i) used[ops[i].kind] = true;
     for (int i = 0; i < n_streams; ++i) {
       // A stream with nothing pending imposes no ordering: skip the event and the barrier packet.
       hipError_t q = hipStreamQuery(reinterpret_cast<hipStream_t>(streams[i]));
@@ -546,7 +550,8 @@ class HipDevice : public Device {
       hipEvent_t ev = dep_events_[dep_cursor_];
       dep_cursor_ = (dep_cursor_ + 1) % kDepEvents;
       if (chk(hipEventRecord(ev, reinterpret_cast<hipStream_t>(streams[i])))) return MW_EHIP;
-      if (chk(hipStreamWaitEvent(data_, ev, 0))) return MW_EHIP;
+      for (uint32_t k = 0; k < kNumKinds; ++k)
+        if (used[k] && chk(hipStreamWaitEvent(data_[k], ev, 0))) return MW_EHIP;
     }
     // split by kind, keep order
     int rc = MW_OK;
@@ -581,7 +586,8 @@ class HipDevice : public Device {
 
   int sync() override {
     if (chk(hipSetDevice(dev_))) return MW_EHIP;
-    if (chk(hipStreamSynchronize(data_))) return MW_EHIP;
+    for (auto& st : data_)
+      if (chk(hipStreamSynchronize(st))) return MW_EHIP;
     if (chk(hipStreamSynchronize(ctl_))) return MW_EHIP;
     return MW_OK;
   }
@@ -685,8 +691,8 @@ class HipDevice : public Device {
       }
       a.first_chunk[n] = (uint32_t)chunks;
       if (chunks == 0 || chunks > 0x7FFFFFFFull) return fail_inval();
-      if (profiling_ && chk(hipEventRecord(e0, data_))) return MW_EHIP;
-      hipLaunchKernelGGL(mw_k_copy, dim3((uint32_t)chunks), dim3(kCopyWG), 0, data_, a, slots_, flags_dev_);
+      if (profiling_ && chk(hipEventRecord(e0, data_[kind]))) return MW_EHIP;
+      hipLaunchKernelGGL(mw_k_copy, dim3((uint32_t)chunks), dim3(kCopyWG), 0, data_[kind], a, slots_, flags_dev_);
     } else {
       CollArgs& a = coll_args_;
       a.n = (uint32_t)n;
@@ -707,20 +713,20 @@ class HipDevice : public Device {
       }
       a.first_chunk[n] = (uint32_t)chunks;
       if (chunks == 0 || chunks > 0x7FFFFFFFull) return fail_inval();
-      if (profiling_ && chk(hipEventRecord(e0, data_))) return MW_EHIP;
+      if (profiling_ && chk(hipEventRecord(e0, data_[kind]))) return MW_EHIP;
       if (kind == kBcast) {
-        hipLaunchKernelGGL(mw_k_bcast, dim3((uint32_t)chunks), dim3(kCopyWG), 0, data_, a, slots_, flags_dev_);
+        hipLaunchKernelGGL(mw_k_bcast, dim3((uint32_t)chunks), dim3(kCopyWG), 0, data_[kind], a, slots_, flags_dev_);
       } else if (cfg_.reduce_lds) {
-        hipLaunchKernelGGL(mw_k_reduce<true>, dim3((uint32_t)chunks), dim3(kReduceWG), 0, data_, a, slots_,
+        hipLaunchKernelGGL(mw_k_reduce<true>, dim3((uint32_t)chunks), dim3(kReduceWG), 0, data_[kind], a, slots_,
                            flags_dev_);
       } else {
-        hipLaunchKernelGGL(mw_k_reduce<false>, dim3((uint32_t)chunks), dim3(kReduceWG), 0, data_, a, slots_,
+        hipLaunchKernelGGL(mw_k_reduce<false>, dim3((uint32_t)chunks), dim3(kReduceWG), 0, data_[kind], a, slots_,
                            flags_dev_);
       }
     }
     if (chk(hipGetLastError())) return MW_EHIP;
     if (profiling_) {
-      if (chk(hipEventRecord(e1, data_))) return MW_EHIP;
+      if (chk(hipEventRecord(e1, data_[kind]))) return MW_EHIP;
       prof_.push_back(ProfRec{kind, e0, e1, total_bytes});
     }
     return MW_OK;
@@ -740,7 +746,8 @@ class HipDevice : public Device {
   RingSlot* slots_ = nullptr;
   uint32_t* flags_host_ = nullptr;
   uint32_t* flags_dev_ = nullptr;
-  hipStream_t data_ = nullptr, ctl_ = nullptr;
+  hipStream_t data_[kNumKinds] = {};  // one per kernel kind
+  hipStream_t ctl_ = nullptr;         // ring-header writes
   std::vector<hipEvent_t> dep_events_;
   int dep_cursor_ = 0;
   bool profiling_ = false;
