@@ -45,7 +45,7 @@ def parse():
     ap.add_argument("--calibrate", type=int, default=0,
                     help="also run this many plain 1 GiB device copies (torch copy_) before the timed region: the "
                          "known-size kernel that hardware counters of a profiling run are scaled by")
-    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "config5"], default="config2",
+    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "config5", "collectives"], default="config2",
                     help="config2 (default) is the headline workload; the others are measured the same way")
     ap.add_argument("--abort-step", type=int, default=100, help="config4: step before which worker 7 is aborted")
     ap.add_argument("--ops", type=int, default=10_000, help="config5: operations in the trace")
@@ -649,6 +649,78 @@ def run_config5(torch, mw, dev, n_ops, reps):
     }
 
 
+def run_collectives(torch, mw, dev, reps):
+    """Large-payload bandwidth of every operation of the communicator: 8 worlds x 4 ranks, 64 MiB fp32 per
+    rank, all worlds outstanding together; kernel time from HIP events on the library's streams."""
+    n, nworlds, S = 4, 8, 64 << 20
+    count = S // 4
+    for w in range(nworlds):
+        mw.mw_world_create(w, list(range(4 * w, 4 * w + 4)))
+    small = [[torch.zeros(S, dtype=torch.uint8, device=dev) for _ in range(n)] for _ in range(nworlds)]
+    big = [[torch.zeros(n * S, dtype=torch.uint8, device=dev) for _ in range(n)] for _ in range(nworlds)]
+    torch.cuda.synchronize()
+    NONE = mw.STREAM_NONE
+    f32 = mw.MW_F32
+
+    def posts_of(kind):
+        out = []
+        for w in range(nworlds):
+            for r in range(n):
+                a, b = small[w][r].data_ptr(), big[w][r].data_ptr()
+                if kind == "send/recv":
+                    if r % 2 == 0:
+                        out.append((mw.POST_SEND, w, r, r + 1, a, count, f32, NONE))
+                        out.append((mw.POST_RECV, w, r, r + 1, small[w][r + 1].data_ptr(), count, f32, NONE))
+                elif kind == "broadcast":
+                    out.append((mw.POST_BROADCAST, w, r, 0, a, count, f32, NONE))
+                elif kind == "all-reduce":
+                    out.append((mw.POST_ALLREDUCE_SUM, w, r, 0, a, count, f32, NONE))
+                elif kind == "reduce":
+                    out.append((mw.POST_REDUCE_SUM, w, r, 0, a, count, f32, NONE))
+                elif kind == "all-gather":
+                    out.append((mw.POST_ALL_GATHER, w, r, 0, a, count, f32, NONE, b))
+                elif kind == "gather":
+                    out.append((mw.POST_GATHER, w, r, 0, a, count, f32, NONE, b if r == 0 else None))
+                else:
+                    out.append((mw.POST_SCATTER, w, r, 0, big[w][0].data_ptr() if r == 0 else None, count, f32, NONE, a))
+        return out
+
+    # algorithmic bytes per collective (per world), kernel kind that runs it
+    table = {"send/recv": (2 * 2 * S, mw.KIND_COPY), "broadcast": (n * S, mw.KIND_BCAST),
+             "all-reduce": (2 * n * S, mw.KIND_REDUCE), "reduce": ((n + 1) * S, mw.KIND_REDUCE),
+             "all-gather": (n * S + n * n * S, mw.KIND_BCAST), "gather": (2 * n * S, mw.KIND_COPY),
+             "scatter": (2 * n * S, mw.KIND_COPY)}
+    res = {}
+    iters = max(3 * reps, 3)
+    for kind, (alg, kk) in table.items():
+        pb = mw.PostBatch(posts_of(kind))
+        for it in range(iters + 2):
+            if it == 2:
+                mw.mw_profile_enable(True)
+                mw.mw_profile_read(kk)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            pb.post()
+            mw.mw_flush()
+            ps = mw.PollSet(list(pb.handles))
+            while ps.poll():
+                pass
+        wall = time.perf_counter() - t0
+        launches, ms, _ = mw.mw_profile_read(kk)
+        mw.mw_profile_enable(False)
+        res[kind] = {"kernel_ms": round(ms / launches, 4), "alg_traffic_GBps": round(nworlds * alg / (ms / launches) / 1e6, 1),
+                     "pct_of_hbm_peak": round(nworlds * alg / (ms / launches) / 1e6 / HBM_PEAK_GBPS * 100, 1),
+                     "end_to_end_GBps": round(iters * nworlds * alg / wall / 1e9, 1)}
+    worst = min(v["alg_traffic_GBps"] for v in res.values())
+    return {
+        "value": res["send/recv"]["end_to_end_GBps"] / 2, "ms_per_step": res["send/recv"]["kernel_ms"], "steps": iters,
+        "config": {"workload": "every operation of the communicator on large payloads: 8 worlds x 4 ranks, 64 MiB fp32 "
+                               "per rank, all worlds outstanding together", "worlds": nworlds, "ranks": n,
+                   "payload_dtype": "f32"},
+        "per_operation": res, "lowest_alg_traffic_GBps": worst, "roofline": None,
+    }
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -675,6 +747,8 @@ def main():
         res = run_config3(torch, mw, dev, args.steps if args.steps != 50 else 500, args.reps, args.reduce_lds)
     elif args.workload == "config1":
         res = run_config1(torch, mw, dev, args.reps)
+    elif args.workload == "collectives":
+        res = run_collectives(torch, mw, dev, args.reps)
     else:
         res = run_config5(torch, mw, dev, args.ops, args.reps)
     mw.mw_shutdown()

@@ -129,6 +129,27 @@ int mw_broadcast(int world_id, int rank, int root_rank, void* buf, size_t count,
 int mw_allreduce_sum(int world_id, int rank, void* buf, size_t count, mw_dtype dtype, void* hip_stream,
                      mw_handle* out);
 
+/* The communicator's other four collectives (Sec. 3.3 lists eight operations), posted once by every
+ * rank like broadcast and all-reduce, sequenced and completed the same way, worlds of at most
+ * MW_MAX_COLL_RANKS ranks.  n = ranks of the world, S = count elements of dtype.
+ *
+ * mw_reduce_sum: root_rank's buffer receives the element-wise sum over the ranks (fp32 accumulation in
+ *   ascending rank order, as all-reduce); every other rank's buffer is only read.
+ * mw_all_gather: every rank's recvbuf (n x S) receives the ranks' sendbufs (S each) concatenated in rank
+ *   order.  A rank may contribute in place (sendbuf == recvbuf + rank x S bytes).
+ * mw_gather: as all-gather, but only root_rank has a recvbuf (pass NULL elsewhere).
+ * mw_scatter: rank r's recvbuf (S) receives slice r of root_rank's sendbuf (n x S); sendbuf is used on
+ *   the root only (pass NULL elsewhere).
+ * The copies are byte-exact. */
+int mw_reduce_sum(int world_id, int rank, int root_rank, void* buf, size_t count, mw_dtype dtype, void* hip_stream,
+                  mw_handle* out);
+int mw_all_gather(int world_id, int rank, const void* sendbuf, void* recvbuf, size_t count, mw_dtype dtype,
+                  void* hip_stream, mw_handle* out);
+int mw_gather(int world_id, int rank, int root_rank, const void* sendbuf, void* recvbuf, size_t count,
+              mw_dtype dtype, void* hip_stream, mw_handle* out);
+int mw_scatter(int world_id, int rank, int root_rank, const void* sendbuf, void* recvbuf, size_t count,
+               mw_dtype dtype, void* hip_stream, mw_handle* out);
+
 /* Status of an operation: MW_DONE, MW_PENDING, MW_BROKEN, or MW_EMISMATCH / MW_EBADHANDLE.  Never
  * blocks and never synchronises the device: completion is read from a host-visible flag that the
  * GPU writes when the operation's last chunk has retired (Sec. 3.2: asynchronous operations need
@@ -145,12 +166,17 @@ int mw_poll(mw_handle h);
 int mw_flush(void);
 
 /* Post many sides with one call (one lock acquisition): posts[i] is what the corresponding
- * mw_send / mw_recv / mw_broadcast / mw_allreduce_sum call would take -- `a`/`b` are src/dst rank for
- * point-to-point, rank/root for broadcast, rank/unused for all-reduce.  Posts are processed in array
+ * mw_send / mw_recv / mw_broadcast / mw_allreduce_sum / mw_reduce_sum / mw_all_gather / mw_gather /
+ * mw_scatter call would take -- `a`/`b` are src/dst rank for point-to-point, rank/root for the rooted
+ * collectives, rank/unused otherwise; buf2 is the recvbuf of all-gather, gather and scatter (buf their
+ * sendbuf).  Posts are processed in array
  * order and independently: handles[i] is the handle, or 0 if that post was refused; results[i] (may be
  * NULL) is its return code.  Returns MW_OK or the first refusal's code.  Host arrays, read/written
  * during the call. */
-typedef enum { MW_POST_SEND = 0, MW_POST_RECV = 1, MW_POST_BROADCAST = 2, MW_POST_ALLREDUCE_SUM = 3 } mw_post_kind;
+typedef enum {
+  MW_POST_SEND = 0, MW_POST_RECV = 1, MW_POST_BROADCAST = 2, MW_POST_ALLREDUCE_SUM = 3,
+  MW_POST_REDUCE_SUM = 4, MW_POST_ALL_GATHER = 5, MW_POST_GATHER = 6, MW_POST_SCATTER = 7
+} mw_post_kind;
 typedef struct {
   int32_t kind; /* mw_post_kind */
   int32_t world_id;
@@ -161,6 +187,7 @@ typedef struct {
   int32_t dtype; /* mw_dtype */
   int32_t reserved;
   void* hip_stream;
+  void* buf2;
 } mw_post_desc;
 int mw_post_many(const mw_post_desc* posts, int n, mw_handle* handles, int* results);
 
@@ -183,7 +210,8 @@ const char* mw_strerror(int err);
 
 /* Per-kernel timing with HIP events on the library's own stream.  mw_profile_enable(1) starts
  * bracketing every data-kernel launch with events; mw_profile_read sums the finished launches of
- * kernel kind `kind` (0 copy, 1 broadcast, 2 all-reduce): number of launches, total milliseconds
+ * kernel kind `kind` (0 copy incl. gather / scatter segments, 1 fan-out: broadcast and all-gather, 2 reduce:
+ * all-reduce and reduce): number of launches, total milliseconds
  * and total payload-descriptor bytes (sum of nbytes over operations).  Reading waits for the
  * recorded events (blocks); it is for benchmarks, not for the data path. */
 int mw_profile_enable(int on);

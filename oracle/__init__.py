@@ -21,6 +21,10 @@ from .mw_oracle import (  # noqa: F401
     allreduce_sum_f64,
     allreduce_sum_ordered,
     allreduce_within_tolerance,
+    reduce_result_f64,
+    all_gather_result,
+    gather_result,
+    scatter_result,
     bf16_bits_to_f32,
     f32_to_bf16_bits,
     broken_worlds_of_worker,

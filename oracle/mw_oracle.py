@@ -13,8 +13,13 @@ written out, processed strictly in program (trace) order with no concurrency:
   are non-blocking: an operation whose peers have not arrived stays pending
   and must not hold up any other world (Sec. 3.2 "Non-blocking CCL
   operations").
-* send/recv, broadcast and all-reduce are the four of the communicator's
-  eight operations covered here (Sec. 3.3 "World Communicator").
+* all eight operations of the communicator are covered: send, recv,
+  broadcast, all-reduce, reduce, all-gather, gather, scatter (Sec. 3.3
+  "World Communicator").  The paper only names them; their meaning is the
+  usual one of collective communication: reduce leaves the sum on the root
+  only, all-gather concatenates every rank's tensor in rank order on every
+  rank, gather does so on the root only, scatter hands slice r of the
+  root's tensor to rank r.
 * when a world is broken the manager fences it off, aborts its pending
   operations and raises to the application; later access is refused
   (Sec. 3.3 "World Manager"); everything that completed before the failure
@@ -147,6 +152,31 @@ def allreduce_sum_ordered(bufs, count, dtype):
     return f32_to_bf16_bits(acc).view(np.uint8).copy()
 
 
+def reduce_result_f64(bufs, count, dtype):
+    """reduce (sum): what the ROOT ends with -- the same sum as all-reduce; every
+    other rank's tensor is left as it was."""
+    return allreduce_sum_f64(bufs, count, dtype)
+
+
+def all_gather_result(send_bufs):
+    """all-gather: every rank receives the ranks' tensors concatenated in rank order."""
+    return np.concatenate([_as_bytes(b) for b in send_bufs])
+
+
+def gather_result(send_bufs):
+    """gather: the root receives the ranks' tensors concatenated in rank order."""
+    return np.concatenate([_as_bytes(b) for b in send_bufs])
+
+
+def scatter_result(root_send, n, rank):
+    """scatter: rank r receives the r-th of n equal slices of the root's tensor."""
+    raw = _as_bytes(root_send)
+    if raw.size % n:
+        raise OracleError("EINVAL", "scatter source is n equal slices")
+    k = raw.size // n
+    return np.array(raw[rank * k : (rank + 1) * k], copy=True)
+
+
 def allreduce_within_tolerance(y_bytes, s, sabs, count, dtype, tol=None):
     """Check a device result y against the float64 sum s.
 
@@ -267,12 +297,17 @@ class WorldOracle:
         return self._post_p2p(False, world, src, dst, buf, count, dtype)
 
     # -- collectives (Sec. 3.3: broadcast, all-reduce) ------------------------
-    def _post_coll(self, kind, world, rank, root, buf, count, dtype):
+    _ROOTED = ("bcast", "reduce", "gather", "scatter")
+
+    def _post_coll(self, kind, world, rank, root, buf, count, dtype, buf2=None, len1=1, len2=0):
+        """buf holds len1*count elements and buf2 (if the kind has one on this rank) len2*count."""
         w = self._world(world)
         n = len(w.members)
-        if not (0 <= rank < n) or (kind == "bcast" and not (0 <= root < n)):
+        if not (0 <= rank < n) or (kind in self._ROOTED and not (0 <= root < n)):
             raise OracleError("EINVAL", "ranks")
-        self._check_buf(buf, count, dtype)
+        self._check_buf(buf, count * len1, dtype)
+        if len2:
+            self._check_buf(buf2, count * len2, dtype)
         if w.state == BROKEN:
             return self._new(BROKEN)
         h = self._new(PENDING)
@@ -282,7 +317,7 @@ class WorldOracle:
         while len(w.coll) <= idx:
             w.coll.append({})
         slot = w.coll[idx]
-        slot[rank] = (h, kind, root, buf, count, dtype)
+        slot[rank] = (h, kind, root, buf, count, dtype, buf2)
         # collectives of a world execute in sequence order once all ranks posted
         while w.coll and len(w.coll[0]) == n:
             self._run_coll(w.coll.popleft(), n)
@@ -299,24 +334,38 @@ class WorldOracle:
             return
         kind, root, count, dtype = next(iter(sig))
         bufs = [p[3] for p in posts]
+        bufs2 = [p[6] for p in posts]
         nb = count * _ITEMSIZE[dtype]
-        if all(b is not None for b in bufs):
+        have = all(b is not None for b in bufs)
+        if kind == "bcast" and have:
             raws = [_as_bytes(b)[:nb] for b in bufs]
-            if kind == "bcast":
-                out = broadcast_result(raws, root)
-                for r in range(n):
-                    if r != root:
-                        raws[r][:] = out[r]
+            out = broadcast_result(raws, root)
+            for r in range(n):
+                if r != root:
+                    raws[r][:] = out[r]
+        elif kind in ("allreduce", "reduce") and have:
+            raws = [_as_bytes(b)[:nb] for b in bufs]
+            s, sabs = allreduce_sum_f64(raws, count, dtype)
+            for r in range(n):
+                if kind == "allreduce" or r == root:
+                    self.reduce_ref[hs[r]] = (s, sabs)
+            if dtype == F32:
+                outb = s.astype(np.float32).view(np.uint8)
             else:
-                s, sabs = allreduce_sum_f64(raws, count, dtype)
-                for h in hs:
-                    self.reduce_ref[h] = (s, sabs)
-                if dtype == F32:
-                    outb = s.astype(np.float32).view(np.uint8)
-                else:
-                    outb = f32_to_bf16_bits(s.astype(np.float32)).view(np.uint8)
-                for r in range(n):
+                outb = f32_to_bf16_bits(s.astype(np.float32)).view(np.uint8)
+            for r in range(n):
+                if kind == "allreduce" or r == root:
                     raws[r][:] = outb
+        elif kind == "allgather" and have and all(b is not None for b in bufs2):
+            cat = all_gather_result([_as_bytes(b)[:nb] for b in bufs])  # taken before any rank is written
+            for r in range(n):
+                _as_bytes(bufs2[r])[: n * nb] = cat
+        elif kind == "gather" and have and bufs2[root] is not None:
+            _as_bytes(bufs2[root])[: n * nb] = gather_result([_as_bytes(b)[:nb] for b in bufs])
+        elif kind == "scatter" and bufs[root] is not None and all(b is not None for b in bufs2):
+            src = np.array(_as_bytes(bufs[root])[: n * nb], copy=True)
+            for r in range(n):
+                _as_bytes(bufs2[r])[:nb] = scatter_result(src, n, r)
         for h in hs:
             self.result[h] = DONE
 
@@ -325,6 +374,29 @@ class WorldOracle:
 
     def post_allreduce(self, world, rank, buf, count, dtype):
         return self._post_coll("allreduce", world, rank, 0, buf, count, dtype)
+
+    def post_reduce(self, world, rank, root, buf, count, dtype):
+        """buf: count elements; the root's is overwritten with the sum, the others are only read."""
+        return self._post_coll("reduce", world, rank, root, buf, count, dtype)
+
+    def post_all_gather(self, world, rank, sendbuf, recvbuf, count, dtype):
+        """sendbuf: count elements; recvbuf: n*count elements on every rank."""
+        n = len(self._world(world).members)
+        return self._post_coll("allgather", world, rank, 0, sendbuf, count, dtype, recvbuf, 1, n)
+
+    def post_gather(self, world, rank, root, sendbuf, recvbuf, count, dtype):
+        """sendbuf: count elements; recvbuf: n*count elements, used on the root only."""
+        n = len(self._world(world).members)
+        is_root = rank == root
+        return self._post_coll("gather", world, rank, root, sendbuf, count, dtype, recvbuf if is_root else None,
+                               1, n if is_root and recvbuf is not None else 0)
+
+    def post_scatter(self, world, rank, root, sendbuf, recvbuf, count, dtype):
+        """sendbuf: n*count elements, used on the root only; recvbuf: count elements on every rank."""
+        n = len(self._world(world).members)
+        is_root = rank == root
+        return self._post_coll("scatter", world, rank, root, sendbuf if is_root else None, count, dtype, recvbuf,
+                               n if is_root else 0, 1)
 
     # -- faults (Sec. 3.1 fault domains; Sec. 3.3 manager aborts pending ops) ---
     def abort_world(self, world):

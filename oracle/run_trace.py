@@ -49,18 +49,29 @@ def run_trace(trace, materialize, data_bufs=None):
         k = op.kind
         if k == "create":
             orc.create(op.world, op.members)
-        elif k in ("send", "recv", "bcast", "allreduce"):
-            b = get(op.buf)
+        elif k in ("send", "recv", "bcast", "allreduce", "reduce", "allgather", "gather", "scatter"):
+            b = get(op.buf) if op.buf >= 0 else None
+            b2 = get(op.buf2) if op.buf2 >= 0 else None
             if k == "send":
                 h = orc.post_send(op.world, op.a, op.b, b, op.count, op.dtype)
             elif k == "recv":
                 h = orc.post_recv(op.world, op.a, op.b, b, op.count, op.dtype)
             elif k == "bcast":
                 h = orc.post_broadcast(op.world, op.a, op.b, b, op.count, op.dtype)
-            else:
+            elif k == "allreduce":
                 h = orc.post_allreduce(op.world, op.a, b, op.count, op.dtype)
+            elif k == "reduce":
+                h = orc.post_reduce(op.world, op.a, op.b, b, op.count, op.dtype)
+            elif k == "allgather":
+                h = orc.post_all_gather(op.world, op.a, b, b2, op.count, op.dtype)
+            elif k == "gather":
+                h = orc.post_gather(op.world, op.a, op.b, b, b2, op.count, op.dtype)
+            else:
+                h = orc.post_scatter(op.world, op.a, op.b, b, b2, op.count, op.dtype)
             handle_of[idx] = h
-            last_post[op.buf] = idx
+            for bid in (op.buf, op.buf2):
+                if bid >= 0:
+                    last_post[bid] = idx
         elif k == "abort_world":
             orc.abort_world(op.world)
         elif k == "abort_worker":
@@ -69,7 +80,7 @@ def run_trace(trace, materialize, data_bufs=None):
             a = get(op.buf)
             out.snapshots[idx] = None if a is None else a.copy()
             p = last_post.get(op.buf)
-            if p is not None and trace.ops[p].kind == "allreduce" and orc.status(handle_of[p]) == DONE:
+            if p is not None and trace.ops[p].kind in ("allreduce", "reduce") and orc.status(handle_of[p]) == DONE:
                 ref = orc.reduce_ref.get(handle_of[p])
                 if ref is not None:
                     out.reduce_ref[idx] = (ref[0], ref[1], trace.ops[p].count, trace.ops[p].dtype)
@@ -89,7 +100,7 @@ def run_trace(trace, materialize, data_bufs=None):
         st = orc.status(h)
         out.status[idx] = st
         op = trace.ops[idx]
-        if st == DONE and (op.kind == "recv" or (op.kind in ("bcast", "allreduce") and op.a == 0)):
+        if st == DONE and (op.kind == "recv" or (op.kind not in ("send", "recv") and op.a == 0)):
             out.payload_bytes_done += op.count * itemsize[op.dtype]
     out.world_state = {w: orc.world_state(w) for w in orc.worlds}
     return out

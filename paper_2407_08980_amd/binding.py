@@ -26,19 +26,21 @@ KIND_COPY, KIND_BCAST, KIND_REDUCE = 0, 1, 2
 
 SYMBOLS = [
     "mw_init", "mw_shutdown", "mw_world_create", "mw_world_abort", "mw_worker_abort", "mw_world_state",
-    "mw_send", "mw_recv", "mw_broadcast", "mw_allreduce_sum", "mw_poll", "mw_flush", "mw_pending_ops", "mw_poll_many", "mw_post_many",
+    "mw_send", "mw_recv", "mw_broadcast", "mw_allreduce_sum", "mw_reduce_sum", "mw_all_gather", "mw_gather",
+    "mw_scatter", "mw_poll", "mw_flush", "mw_pending_ops", "mw_poll_many", "mw_post_many",
     "mw_config_set", "mw_config_get", "mw_handle_capacity", "mw_last_hip_error", "mw_strerror",
     "mw_profile_enable", "mw_profile_read", "mw_debug_ring_read", "mw_debug_arena_hash",
 ]
 
 
 POST_SEND, POST_RECV, POST_BROADCAST, POST_ALLREDUCE_SUM = 0, 1, 2, 3
+POST_REDUCE_SUM, POST_ALL_GATHER, POST_GATHER, POST_SCATTER = 4, 5, 6, 7
 
 
 class PostDesc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("world_id", C.c_int32), ("a", C.c_int32), ("b", C.c_int32),
                 ("buf", C.c_void_p), ("count", C.c_uint64), ("dtype", C.c_int32), ("reserved", C.c_int32),
-                ("hip_stream", C.c_void_p)]
+                ("hip_stream", C.c_void_p), ("buf2", C.c_void_p)]
 
 
 class MwError(RuntimeError):
@@ -63,6 +65,10 @@ def declare(lib):
         f.argtypes = [i, i, i, vp, sz, i, vp, u64p]
     lib.mw_broadcast.argtypes = [i, i, i, vp, sz, i, vp, u64p]
     lib.mw_allreduce_sum.argtypes = [i, i, vp, sz, i, vp, u64p]
+    lib.mw_reduce_sum.argtypes = [i, i, i, vp, sz, i, vp, u64p]
+    lib.mw_all_gather.argtypes = [i, i, vp, vp, sz, i, vp, u64p]
+    lib.mw_gather.argtypes = [i, i, i, vp, vp, sz, i, vp, u64p]
+    lib.mw_scatter.argtypes = [i, i, i, vp, vp, sz, i, vp, u64p]
     lib.mw_poll.argtypes = [C.c_uint64]
     lib.mw_flush.argtypes = []
     lib.mw_pending_ops.argtypes = []
@@ -162,6 +168,32 @@ def mw_allreduce_sum(world, rank, buf, count, dtype, stream=0):
     return h.value
 
 
+def mw_reduce_sum(world, rank, root_rank, buf, count, dtype, stream=0):
+    h = C.c_uint64(0)
+    _ck(lib().mw_reduce_sum(world, rank, root_rank, buf, count, dtype, _stream(stream), C.byref(h)), "mw_reduce_sum")
+    return h.value
+
+
+def mw_all_gather(world, rank, sendbuf, recvbuf, count, dtype, stream=0):
+    h = C.c_uint64(0)
+    _ck(lib().mw_all_gather(world, rank, sendbuf, recvbuf, count, dtype, _stream(stream), C.byref(h)), "mw_all_gather")
+    return h.value
+
+
+def mw_gather(world, rank, root_rank, sendbuf, recvbuf, count, dtype, stream=0):
+    """recvbuf: None on every rank but the root."""
+    h = C.c_uint64(0)
+    _ck(lib().mw_gather(world, rank, root_rank, sendbuf, recvbuf, count, dtype, _stream(stream), C.byref(h)), "mw_gather")
+    return h.value
+
+
+def mw_scatter(world, rank, root_rank, sendbuf, recvbuf, count, dtype, stream=0):
+    """sendbuf: None on every rank but the root."""
+    h = C.c_uint64(0)
+    _ck(lib().mw_scatter(world, rank, root_rank, sendbuf, recvbuf, count, dtype, _stream(stream), C.byref(h)), "mw_scatter")
+    return h.value
+
+
 def mw_poll(handle):
     return lib().mw_poll(handle)
 
@@ -188,13 +220,15 @@ class PollSet:
 
 
 class PostBatch:
-    """A reusable array of posts for mw_post_many: (kind, world, a, b, buf, count, dtype, stream) tuples."""
+    """A reusable array of posts for mw_post_many: (kind, world, a, b, buf, count, dtype, stream[, buf2]) tuples."""
 
     def __init__(self, posts):
         self.n = len(posts)
         self.descs = (PostDesc * self.n)()
-        for d, (kind, world, a, b, buf, count, dtype, stream) in zip(self.descs, posts):
+        for d, p in zip(self.descs, posts):
+            kind, world, a, b, buf, count, dtype, stream = p[:8]
             d.kind, d.world_id, d.a, d.b, d.buf, d.count, d.dtype = kind, world, a, b, buf, count, dtype
+            d.buf2 = p[8] if len(p) > 8 else None
             d.hip_stream = stream if stream != STREAM_NONE else C.c_void_p(-1).value
         self.handles = (C.c_uint64 * self.n)()
         self.results = (C.c_int * self.n)()

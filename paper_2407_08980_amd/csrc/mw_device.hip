@@ -46,18 +46,25 @@ constexpr int kCopyU = 4;       // 16-byte vectors in flight per thread
 #endif
 constexpr int kReduceWG = MW_REDUCE_WG;  // threads per workgroup, all-reduce
 constexpr int kReduceU = MW_REDUCE_U;    // 16-byte vectors per rank in flight per thread
-constexpr int kCopyMax = 80;    // operations per copy launch (kernel arguments stay under 4 KiB)
-constexpr int kCollMax = 36;    // operations per broadcast / all-reduce launch
+constexpr int kCopyMax = 72;    // entries per copy launch (kernel arguments stay under 4 KiB)
+constexpr int kCollMax = 36;    // entries per fan-out / reduce launch
 
+// An operation is one or more *entries* of one kernel: a copy is one copy entry, a gather or a
+// scatter n copy entries, a broadcast one fan-out entry, an all-gather n (or more) fan-out entries,
+// an (all-)reduce one reduce entry.  All entries of an operation share its ring slot; `op_chunks`
+// is the chunk count of the whole operation, which is what the arrival counter runs up to.
+// flags: bit 0 = this entry journals the descriptor; bits 8-15 = OpKind; bits 16-23 = ranks;
+// bits 24-31 = mask of the ranks whose buffer a reduce entry stores to.
 struct CopyEnt {
   uint64_t src, dst, nbytes;
   uint32_t slot, gen;
   uint32_t world_id, world_epoch;  // journalled only
+  uint32_t op_chunks, flags;
 };
 struct CopyArgs {
   uint32_t n;
   uint32_t chunk_shift;
-  uint32_t first_chunk[kCopyMax + 1];  // first_chunk[i] = chunks before operation i; [n] = total
+  uint32_t first_chunk[kCopyMax + 1];  // first_chunk[i] = chunks before entry i; [n] = total
   uint32_t pad;
   CopyEnt e[kCopyMax];
 };
@@ -68,6 +75,7 @@ struct CollEnt {
   uint64_t nbytes;
   uint32_t slot, gen, nbuf, dtype;
   uint32_t world_id, world_epoch;  // journalled only
+  uint32_t op_chunks, flags;
 };
 struct CollArgs {
   uint32_t n;
@@ -203,18 +211,18 @@ __global__ __launch_bounds__(kCopyWG) void mw_k_copy(const CopyArgs a, RingSlot*
   const uint64_t src = a.e[op].src, dst = a.e[op].dst, nbytes = a.e[op].nbytes;
   const uint32_t slot = a.e[op].slot, gen = a.e[op].gen;
   const uint32_t ci = c - a.first_chunk[op];
-  const uint32_t nchunks = a.first_chunk[op + 1] - a.first_chunk[op];
+  const uint32_t nchunks = a.e[op].op_chunks, flags = a.e[op].flags;
   const uint64_t off = (uint64_t)ci << a.chunk_shift;
   const uint64_t chunk = 1ull << a.chunk_shift;
   const uint64_t len = (nbytes - off < chunk) ? nbytes - off : chunk;
-  if (ci == 0 && threadIdx.x == 0) {  // journal the descriptor into the world's ring
+  if (ci == 0 && threadIdx.x == 0 && (flags & 1u)) {  // journal the descriptor into the world's ring
     SlotDesc* d = &slots[slot].d;
     d->buf[0] = src;
     d->buf[1] = dst;
     d->nbytes = nbytes;
-    d->kind = kCopy;
+    d->kind = (flags >> 8) & 0xFFu;
     d->dtype = 0;
-    d->nbuf = 2;
+    d->nbuf = (flags >> 16) & 0xFFu;
     d->world_id = a.e[op].world_id;
     d->world_epoch = a.e[op].world_epoch;
     d->gen = gen;
@@ -236,7 +244,7 @@ __global__ __launch_bounds__(kCopyWG) void mw_k_bcast(const CollArgs a, RingSlot
   const uint64_t nbytes = a.e[op].nbytes;
   const uint32_t slot = a.e[op].slot, gen = a.e[op].gen, nbuf = a.e[op].nbuf;
   const uint32_t ci = c - a.first_chunk[op];
-  const uint32_t nchunks = a.first_chunk[op + 1] - a.first_chunk[op];
+  const uint32_t nchunks = a.e[op].op_chunks, flags = a.e[op].flags;
   const uint64_t off = (uint64_t)ci << a.chunk_shift;
   const uint64_t chunk = 1ull << a.chunk_shift;
   const uint64_t len = (nbytes - off < chunk) ? nbytes - off : chunk;
@@ -244,14 +252,14 @@ __global__ __launch_bounds__(kCopyWG) void mw_k_bcast(const CollArgs a, RingSlot
 #pragma unroll
   for (int k = 0; k < kMaxBufs - 1; ++k)
     dp[k] = (k + 1 < (int)nbuf) ? reinterpret_cast<unsigned char*>(a.e[op].buf[k + 1] + off) : nullptr;
-  if (ci == 0 && threadIdx.x == 0) {
+  if (ci == 0 && threadIdx.x == 0 && (flags & 1u)) {
     SlotDesc* d = &slots[slot].d;
 #pragma unroll
     for (int k = 0; k < kMaxBufs; ++k) d->buf[k] = (k < (int)nbuf) ? a.e[op].buf[k] : 0;
     d->nbytes = nbytes;
-    d->kind = kBcast;
+    d->kind = (flags >> 8) & 0xFFu;
     d->dtype = a.e[op].dtype;
-    d->nbuf = nbuf;
+    d->nbuf = (flags >> 16) & 0xFFu;
     d->world_id = a.e[op].world_id;
     d->world_epoch = a.e[op].world_epoch;
     d->gen = gen;
@@ -312,7 +320,8 @@ struct Acc<true> {
 
 // Register path: every thread holds U vectors of one rank at a time and folds them in.
 template <bool BF16, int NB>
-__device__ __forceinline__ void reduce_vectors(const uint64_t* buf, int nbuf, uint64_t off, uint64_t nvec) {
+__device__ __forceinline__ void reduce_vectors(const uint64_t* buf, int nbuf, uint32_t wmask, uint64_t off,
+                                               uint64_t nvec) {
   constexpr int U = kReduceU;
   const uint64_t step = (uint64_t)kReduceWG * U;
   for (uint64_t i = threadIdx.x; i < nvec; i += step) {
@@ -340,7 +349,7 @@ __device__ __forceinline__ void reduce_vectors(const uint64_t* buf, int nbuf, ui
     }
 #pragma unroll
     for (int r = 0; r < NB; ++r) {
-      if (r < nbuf) {
+      if (r < nbuf && ((wmask >> r) & 1u)) {
         u32x4* p = reinterpret_cast<u32x4*>(buf[r] + off);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -356,8 +365,8 @@ __device__ __forceinline__ void reduce_vectors(const uint64_t* buf, int nbuf, ui
 // then each thread sums its column across the staged rank tiles and writes all ranks.  The
 // staging decouples the (n x tile) read burst from the arithmetic and the write burst.
 template <bool BF16>
-__device__ __forceinline__ void reduce_vectors_lds(const uint64_t* buf, int nbuf, uint64_t off, uint64_t nvec,
-                                                   u32x4* tile) {
+__device__ __forceinline__ void reduce_vectors_lds(const uint64_t* buf, int nbuf, uint32_t wmask, uint64_t off,
+                                                   uint64_t nvec, u32x4* tile) {
   constexpr int U = kReduceU;
   const uint64_t step = (uint64_t)kReduceWG * U;
   for (uint64_t base = 0; base < nvec; base += step) {
@@ -379,6 +388,7 @@ __device__ __forceinline__ void reduce_vectors_lds(const uint64_t* buf, int nbuf
       y[u] = acc.out();
     }
     for (int r = 0; r < nbuf; ++r) {
+      if (!((wmask >> r) & 1u)) continue;
       u32x4* p = reinterpret_cast<u32x4*>(buf[r] + off);
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -392,19 +402,21 @@ __device__ __forceinline__ void reduce_vectors_lds(const uint64_t* buf, int nbuf
 
 // Element-wise path for tails and for buffers that are not 16-byte aligned.
 template <bool BF16>
-__device__ __forceinline__ void reduce_scalar(const uint64_t* buf, int nbuf, uint64_t off, uint64_t first,
-                                              uint64_t nelem) {
+__device__ __forceinline__ void reduce_scalar(const uint64_t* buf, int nbuf, uint32_t wmask, uint64_t off,
+                                              uint64_t first, uint64_t nelem) {
   for (uint64_t i = first + threadIdx.x; i < nelem; i += kReduceWG) {
     float acc;
     if (BF16) {
       acc = bf16_to_f32(reinterpret_cast<const uint16_t*>(buf[0] + off)[i]);
       for (int r = 1; r < nbuf; ++r) acc += bf16_to_f32(reinterpret_cast<const uint16_t*>(buf[r] + off)[i]);
       uint16_t o = (uint16_t)f32_to_bf16(acc);
-      for (int r = 0; r < nbuf; ++r) st_stream(reinterpret_cast<uint16_t*>(buf[r] + off) + i, o);
+      for (int r = 0; r < nbuf; ++r)
+        if ((wmask >> r) & 1u) st_stream(reinterpret_cast<uint16_t*>(buf[r] + off) + i, o);
     } else {
       acc = reinterpret_cast<const float*>(buf[0] + off)[i];
       for (int r = 1; r < nbuf; ++r) acc += reinterpret_cast<const float*>(buf[r] + off)[i];
-      for (int r = 0; r < nbuf; ++r) st_stream(reinterpret_cast<float*>(buf[r] + off) + i, acc);
+      for (int r = 0; r < nbuf; ++r)
+        if ((wmask >> r) & 1u) st_stream(reinterpret_cast<float*>(buf[r] + off) + i, acc);
     }
   }
 }
@@ -418,7 +430,8 @@ __global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs a, RingS
   const uint64_t nbytes = a.e[op].nbytes;
   const uint32_t slot = a.e[op].slot, gen = a.e[op].gen, nbuf = a.e[op].nbuf, dtype = a.e[op].dtype;
   const uint32_t ci = c - a.first_chunk[op];
-  const uint32_t nchunks = a.first_chunk[op + 1] - a.first_chunk[op];
+  const uint32_t nchunks = a.e[op].op_chunks, flags = a.e[op].flags;
+  const uint32_t wmask = flags >> 24;  // ranks whose buffer receives the sum (all of them, or the root only)
   const uint64_t off = (uint64_t)ci << a.chunk_shift;
   const uint64_t chunk = 1ull << a.chunk_shift;
   const uint64_t len = (nbytes - off < chunk) ? nbytes - off : chunk;
@@ -426,12 +439,12 @@ __global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs a, RingS
   uint64_t align = 0;
 #pragma unroll
   for (int k = 0; k < kMaxBufs; ++k) align |= buf[k];
-  if (ci == 0 && threadIdx.x == 0) {
+  if (ci == 0 && threadIdx.x == 0 && (flags & 1u)) {
     SlotDesc* d = &slots[slot].d;
 #pragma unroll
     for (int k = 0; k < kMaxBufs; ++k) d->buf[k] = buf[k];
     d->nbytes = nbytes;
-    d->kind = kReduce;
+    d->kind = (flags >> 8) & 0xFFu;
     d->dtype = dtype;
     d->nbuf = nbuf;
     d->world_id = a.e[op].world_id;
@@ -447,23 +460,23 @@ __global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs a, RingS
   if ((align & 15) == 0) {
     nvec = len >> 4;
     if (LDS) {
-      if (bf16) reduce_vectors_lds<true>(buf, (int)nbuf, off, nvec, tile);
-      else reduce_vectors_lds<false>(buf, (int)nbuf, off, nvec, tile);
+      if (bf16) reduce_vectors_lds<true>(buf, (int)nbuf, wmask, off, nvec, tile);
+      else reduce_vectors_lds<false>(buf, (int)nbuf, wmask, off, nvec, tile);
     } else if (nbuf <= 2) {
-      if (bf16) reduce_vectors<true, 2>(buf, (int)nbuf, off, nvec);
-      else reduce_vectors<false, 2>(buf, (int)nbuf, off, nvec);
+      if (bf16) reduce_vectors<true, 2>(buf, (int)nbuf, wmask, off, nvec);
+      else reduce_vectors<false, 2>(buf, (int)nbuf, wmask, off, nvec);
     } else if (nbuf <= 4) {
-      if (bf16) reduce_vectors<true, 4>(buf, (int)nbuf, off, nvec);
-      else reduce_vectors<false, 4>(buf, (int)nbuf, off, nvec);
+      if (bf16) reduce_vectors<true, 4>(buf, (int)nbuf, wmask, off, nvec);
+      else reduce_vectors<false, 4>(buf, (int)nbuf, wmask, off, nvec);
     } else {
-      if (bf16) reduce_vectors<true, kMaxBufs>(buf, (int)nbuf, off, nvec);
-      else reduce_vectors<false, kMaxBufs>(buf, (int)nbuf, off, nvec);
+      if (bf16) reduce_vectors<true, kMaxBufs>(buf, (int)nbuf, wmask, off, nvec);
+      else reduce_vectors<false, kMaxBufs>(buf, (int)nbuf, wmask, off, nvec);
     }
   }
   const uint64_t first = nvec * (16 / isz);
   if (first < nelem) {
-    if (bf16) reduce_scalar<true>(buf, (int)nbuf, off, first, nelem);
-    else reduce_scalar<false>(buf, (int)nbuf, off, first, nelem);
+    if (bf16) reduce_scalar<true>(buf, (int)nbuf, wmask, off, first, nelem);
+    else reduce_scalar<false>(buf, (int)nbuf, wmask, off, first, nelem);
   }
   retire_chunk(slots, host_flags, slot, gen, nchunks);
 }
@@ -538,7 +551,7 @@ class HipDevice : public Device {
     // Each kernel kind has its own stream so that a copy, a broadcast and an all-reduce launch of one
     // flush overlap.  Order every stream used by this flush after the callers' busy streams.
     bool used[kNumKinds] = {};
-    for (int i = 0; i < n; ++i) used[ops[i].kind] = true;
+    for (int i = 0; i < n; ++i) used[kernel_of(ops[i].kind)] = true;
     for (int i = 0; i < n_streams; ++i) {
       // A stream with nothing pending imposes no ordering: skip the event and the barrier packet.
       hipError_t q = hipStreamQuery(reinterpret_cast<hipStream_t>(streams[i]));
@@ -553,15 +566,29 @@ class HipDevice : public Device {
       for (uint32_t k = 0; k < kNumKinds; ++k)
         if (used[k] && chk(hipStreamWaitEvent(data_[k], ev, 0))) return MW_EHIP;
     }
-    // split by kind, keep order
+    // Expand every operation into the entries of its kernel and launch them kind by kind.  All
+    // entries of an operation stay in one launch (they share one chunk size and one arrival count).
     int rc = MW_OK;
     for (uint32_t kind = 0; kind < kNumKinds && rc == MW_OK; ++kind) {
-      idx_.clear();
-      for (int i = 0; i < n; ++i)
-        if (ops[i].kind == kind) idx_.push_back(i);
+      if (!used[kind]) continue;
       const size_t cap = kind == kCopy ? kCopyMax : kCollMax;
-      for (size_t at = 0; at < idx_.size() && rc == MW_OK; at += cap)
-        rc = launch_kind(kind, ops, idx_.data() + at, (int)std::min(cap, idx_.size() - at));
+      ents_.clear();
+      for (int i = 0; i < n && rc == MW_OK; ++i) {
+        if (kernel_of(ops[i].kind) != kind) continue;
+        const size_t before = ents_.size();
+        expand(ops[i], (uint32_t)i);
+        if (ents_.size() == before) {  // every segment already in place: nothing to move, complete now
+          __atomic_store_n(&flags_host_[ops[i].slot], ops[i].gen, __ATOMIC_RELEASE);
+          continue;
+        }
+        if (ents_.size() > cap) {  // launch what was gathered before this operation, keep its entries
+          one_.assign(ents_.begin() + (long)before, ents_.end());
+          ents_.resize(before);
+          rc = launch_entries(kind);
+          ents_.swap(one_);
+        }
+      }
+      if (rc == MW_OK && !ents_.empty()) rc = launch_entries(kind);
     }
     return rc;
   }
@@ -669,59 +696,157 @@ class HipDevice : public Device {
     return std::min(hi, std::max(lo, s));
   }
 
-  int launch_kind(uint32_t kind, const LaunchOp* ops, const int* idx, int n) {
+  struct Ent {  // one kernel entry of an operation
+    uint64_t buf[kMaxBufs];
+    uint64_t nbytes;
+    uint32_t nbuf, dtype, slot, gen, world_id, world_epoch, flags, group;
+  };
+
+  static Kind kernel_of(uint32_t op_kind) {
+    switch (op_kind) {
+      case opCopy: case opGather: case opScatter: return kCopy;
+      case opBcast: case opAllGather: return kBcast;
+      default: return kReduce;
+    }
+  }
+
+  void push_ent(const LaunchOp& o, uint32_t group, const uint64_t* bufs, uint32_t nbuf, uint32_t wmask) {
+    Ent e{};
+    for (uint32_t k = 0; k < nbuf; ++k) e.buf[k] = bufs[k];
+    e.nbytes = o.nbytes;
+    e.nbuf = nbuf;
+    e.dtype = o.dtype;
+    e.slot = o.slot;
+    e.gen = o.gen;
+    e.world_id = o.world_id;
+    e.world_epoch = o.world_epoch;
+    e.group = group;
+    const bool first = ents_.empty() || ents_.back().group != group;
+    e.flags = (first ? 1u : 0u) | (o.kind << 8) | (o.nbuf << 16) | (wmask << 24);
+    ents_.push_back(e);
+  }
+
+  // The kernel entries of one operation (see LaunchOp for the buffer layouts).
+  void expand(const LaunchOp& o, uint32_t group) {
+    const uint32_t n = o.nbuf;
+    uint64_t b[kMaxBufs];
+    switch (o.kind) {
+      case opCopy:
+        push_ent(o, group, o.buf, 2, 0);
+        break;
+      case opBcast:
+        push_ent(o, group, o.buf, n, 0);
+        break;
+      case opAllReduce:
+        push_ent(o, group, o.buf, n, (1u << n) - 1);
+        break;
+      case opReduce:
+        push_ent(o, group, o.buf, n, 1u << o.root);
+        break;
+      case opGather:  // rank q's tensor -> slice q of the root's destination
+        for (uint32_t q = 0; q < n; ++q) {
+          b[0] = o.buf[q];
+          b[1] = o.buf[8] + q * o.nbytes;
+          if (b[0] != b[1]) push_ent(o, group, b, 2, 0);
+        }
+        break;
+      case opScatter:  // slice r of the root's source -> rank r's tensor
+        for (uint32_t r = 0; r < n; ++r) {
+          b[0] = o.buf[0] + r * o.nbytes;
+          b[1] = o.buf[8 + r];
+          if (b[0] != b[1]) push_ent(o, group, b, 2, 0);
+        }
+        break;
+      case opAllGather:  // rank q's tensor is read once and fanned out to slice q of every destination
+        for (uint32_t q = 0; q < n; ++q) {
+          uint32_t k = 1;
+          b[0] = o.buf[q];
+          for (uint32_t r = 0; r < n; ++r) {
+            const uint64_t d = o.buf[8 + r] + q * o.nbytes;
+            if (d == b[0]) continue;  // contribution already in place
+            b[k++] = d;
+            if (k == kMaxBufs) {
+              push_ent(o, group, b, k, 0);
+              k = 1;
+            }
+          }
+          if (k > 1) push_ent(o, group, b, k, 0);
+        }
+        break;
+      default:
+        break;
+    }
+  }
+
+  // Launch the gathered entries (ents_) as one kernel of `kind`.
+  int launch_entries(uint32_t kind) {
+    const int n = (int)ents_.size();
     uint64_t total_bytes = 0;
-    for (int i = 0; i < n; ++i) total_bytes += ops[idx[i]].nbytes;
+    for (const Ent& e : ents_) total_bytes += e.nbytes;
     const uint32_t shift = pick_chunk_shift(kind, total_bytes);
+    // chunks per entry, and per operation (= run of entries with the same group)
+    chunks_.resize((size_t)n);
     uint64_t chunks = 0;
+    for (int i = 0; i < n; ++i) {
+      chunks_[(size_t)i] = (uint32_t)((ents_[(size_t)i].nbytes + (1ull << shift) - 1) >> shift);
+      chunks += chunks_[(size_t)i];
+    }
+    if (chunks == 0 || chunks > 0x7FFFFFFFull) return fail_inval();
+    op_chunks_.resize((size_t)n);
+    for (int i = 0; i < n;) {
+      int j = i;
+      uint32_t sum = 0;
+      while (j < n && ents_[(size_t)j].group == ents_[(size_t)i].group) sum += chunks_[(size_t)j++];
+      for (int k = i; k < j; ++k) op_chunks_[(size_t)k] = sum;
+      i = j;
+    }
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (profiling_) {
       e0 = prof_event();
       e1 = prof_event();
+      if (chk(hipEventRecord(e0, data_[kind]))) return MW_EHIP;
     }
+    uint32_t at = 0;
     if (kind == kCopy) {
       CopyArgs& a = copy_args_;
       a.n = (uint32_t)n;
       a.chunk_shift = shift;
       for (int i = 0; i < n; ++i) {
-        const LaunchOp& o = ops[idx[i]];
-        a.first_chunk[i] = (uint32_t)chunks;
-        chunks += (o.nbytes + (1ull << shift) - 1) >> shift;
-        a.e[i] = CopyEnt{o.buf[0], o.buf[1], o.nbytes, o.slot, o.gen, o.world_id, o.world_epoch};
+        const Ent& e = ents_[(size_t)i];
+        a.first_chunk[i] = at;
+        at += chunks_[(size_t)i];
+        a.e[i] = CopyEnt{e.buf[0], e.buf[1], e.nbytes, e.slot, e.gen, e.world_id, e.world_epoch,
+                         op_chunks_[(size_t)i], e.flags};
       }
-      a.first_chunk[n] = (uint32_t)chunks;
-      if (chunks == 0 || chunks > 0x7FFFFFFFull) return fail_inval();
-      if (profiling_ && chk(hipEventRecord(e0, data_[kind]))) return MW_EHIP;
-      hipLaunchKernelGGL(mw_k_copy, dim3((uint32_t)chunks), dim3(kCopyWG), 0, data_[kind], a, slots_, flags_dev_);
+      a.first_chunk[n] = at;
+      hipLaunchKernelGGL(mw_k_copy, dim3(at), dim3(kCopyWG), 0, data_[kind], a, slots_, flags_dev_);
     } else {
       CollArgs& a = coll_args_;
       a.n = (uint32_t)n;
       a.chunk_shift = shift;
       for (int i = 0; i < n; ++i) {
-        const LaunchOp& o = ops[idx[i]];
-        a.first_chunk[i] = (uint32_t)chunks;
-        chunks += (o.nbytes + (1ull << shift) - 1) >> shift;
-        CollEnt& e = a.e[i];
-        for (int k = 0; k < kMaxBufs; ++k) e.buf[k] = k < (int)o.nbuf ? o.buf[k] : 0;
-        e.nbytes = o.nbytes;
-        e.slot = o.slot;
-        e.gen = o.gen;
-        e.nbuf = o.nbuf;
-        e.dtype = o.dtype;
-        e.world_id = o.world_id;
-        e.world_epoch = o.world_epoch;
+        const Ent& e = ents_[(size_t)i];
+        a.first_chunk[i] = at;
+        at += chunks_[(size_t)i];
+        CollEnt& c = a.e[i];
+        for (int k = 0; k < kMaxBufs; ++k) c.buf[k] = e.buf[k];
+        c.nbytes = e.nbytes;
+        c.slot = e.slot;
+        c.gen = e.gen;
+        c.nbuf = e.nbuf;
+        c.dtype = e.dtype;
+        c.world_id = e.world_id;
+        c.world_epoch = e.world_epoch;
+        c.op_chunks = op_chunks_[(size_t)i];
+        c.flags = e.flags;
       }
-      a.first_chunk[n] = (uint32_t)chunks;
-      if (chunks == 0 || chunks > 0x7FFFFFFFull) return fail_inval();
-      if (profiling_ && chk(hipEventRecord(e0, data_[kind]))) return MW_EHIP;
+      a.first_chunk[n] = at;
       if (kind == kBcast) {
-        hipLaunchKernelGGL(mw_k_bcast, dim3((uint32_t)chunks), dim3(kCopyWG), 0, data_[kind], a, slots_, flags_dev_);
+        hipLaunchKernelGGL(mw_k_bcast, dim3(at), dim3(kCopyWG), 0, data_[kind], a, slots_, flags_dev_);
       } else if (cfg_.reduce_lds) {
-        hipLaunchKernelGGL(mw_k_reduce<true>, dim3((uint32_t)chunks), dim3(kReduceWG), 0, data_[kind], a, slots_,
-                           flags_dev_);
+        hipLaunchKernelGGL(mw_k_reduce<true>, dim3(at), dim3(kReduceWG), 0, data_[kind], a, slots_, flags_dev_);
       } else {
-        hipLaunchKernelGGL(mw_k_reduce<false>, dim3((uint32_t)chunks), dim3(kReduceWG), 0, data_[kind], a, slots_,
-                           flags_dev_);
+        hipLaunchKernelGGL(mw_k_reduce<false>, dim3(at), dim3(kReduceWG), 0, data_[kind], a, slots_, flags_dev_);
       }
     }
     if (chk(hipGetLastError())) return MW_EHIP;
@@ -729,6 +854,7 @@ class HipDevice : public Device {
       if (chk(hipEventRecord(e1, data_[kind]))) return MW_EHIP;
       prof_.push_back(ProfRec{kind, e0, e1, total_bytes});
     }
+    ents_.clear();
     return MW_OK;
   }
 
@@ -754,7 +880,8 @@ class HipDevice : public Device {
   std::vector<ProfRec> prof_;
   std::vector<hipEvent_t> prof_free_;
   ProfAcc acc_[kNumKinds];
-  std::vector<int> idx_;
+  std::vector<Ent> ents_, one_;
+  std::vector<uint32_t> chunks_, op_chunks_;
   CopyArgs copy_args_{};
   CollArgs coll_args_{};
 };

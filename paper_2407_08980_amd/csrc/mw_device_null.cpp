@@ -97,9 +97,9 @@ int mwt_pending(void) { return g_null ? (int)g_null->pending.size() : -1; }
 int mwt_marks(void) { return g_null ? g_null->marks : -1; }
 int mwt_log_size(void) { return g_null ? (int)g_null->log.size() : -1; }
 
-// Fields of the i-th operation ever launched: out[0..7] = buffers, out[8] = nbytes, out[9] = kind,
+// Fields of the i-th operation ever launched: out[0..7] = buffers 0..7, out[8] = nbytes, out[9] = kind,
 // out[10] = dtype, out[11] = nbuf, out[12] = slot, out[13] = gen, out[14] = world id, out[15] = epoch,
-// out[16] = launch id.
+// out[16] = launch id, out[17] = root, out[18..25] = buffers 8..15.
 int mwt_log_entry(int i, uint64_t* out) {
   if (!g_null || i < 0 || i >= (int)g_null->log.size()) return -1;
   const Recorded& r = g_null->log[i];
@@ -113,6 +113,8 @@ int mwt_log_entry(int i, uint64_t* out) {
   out[14] = r.op.world_id;
   out[15] = r.op.world_epoch;
   out[16] = (uint64_t)r.launch_id;
+  out[17] = r.op.root;
+  for (int k = 0; k < kMaxBufs; ++k) out[18 + k] = r.op.buf[kMaxBufs + k];
   return 0;
 }
 

@@ -32,6 +32,7 @@ struct Post {  // one posted side that has not met its peers yet
   uint64_t count;
   uint32_t dtype;
   void* stream;
+  uint64_t buf2;  // second buffer of all-gather / gather / scatter posts
 };
 
 struct PairQ {
@@ -244,9 +245,9 @@ int flush_locked(Context& c) {
   return MW_OK;
 }
 
-// An operation with all sides present: give it a record and queue it for the next launch.
-int enqueue_op(Context& c, uint32_t wi, uint32_t kind, uint32_t dtype, uint64_t nbytes, const Post* posts,
-               int n_posts, const int* buf_order) {
+// An operation with all sides present: give it a record and queue it for the next launch.  `l` has
+// kind, dtype, nbytes, nbuf, root and the buffers filled in; `posts` are its sides (handles, streams).
+int enqueue_op(Context& c, uint32_t wi, const LaunchOp& l, const Post* posts, int n_posts) {
   uint32_t opi;
   if (!c.free_ops.empty()) {
     opi = c.free_ops.back();
@@ -259,14 +260,10 @@ int enqueue_op(Context& c, uint32_t wi, uint32_t kind, uint32_t dtype, uint64_t 
   std::memset(&op, 0, sizeof(op));
   op.world = wi;
   op.state = kOpQueued;
-  op.l.kind = kind;
-  op.l.dtype = dtype;
-  op.l.nbytes = nbytes;
-  op.l.nbuf = (uint32_t)n_posts;
+  op.l = l;
   op.l.world_id = (uint32_t)c.worlds[wi]->id;
   for (int i = 0; i < n_posts; ++i) {
-    const Post& p = posts[buf_order[i]];
-    op.l.buf[i] = p.buf;
+    const Post& p = posts[i];
     op.handles[op.n_handles++] = p.hslot;
     c.handles[p.hslot].op = opi;
     if (p.stream != MW_STREAM_NONE) {
@@ -298,7 +295,7 @@ int post_p2p_locked(Context& c, bool is_send, int world_id, int src, int dst, co
   int rc = alloc_handle(c, &hs);
   if (rc != MW_OK) return rc;
   *out = make_handle(hs, c.handles[hs].gen);
-  Post me{hs, (uint64_t)(uintptr_t)buf, (uint64_t)count, (uint32_t)dtype, stream};
+  Post me{hs, (uint64_t)(uintptr_t)buf, (uint64_t)count, (uint32_t)dtype, stream, 0};
   PairQ& q = w.pairs[(uint32_t)src * MW_MAX_RANKS + (uint32_t)dst];
   std::deque<Post>& theirs = is_send ? q.recvs : q.sends;
   if (theirs.empty()) {
@@ -318,12 +315,25 @@ int post_p2p_locked(Context& c, bool is_send, int world_id, int src, int dst, co
     return MW_OK;
   }
   Post pair[2] = {is_send ? me : other, is_send ? other : me};  // {send side, recv side}
-  const int order[2] = {0, 1};
-  return enqueue_op(c, it->second, kCopy, (uint32_t)dtype, count * item_size(dtype), pair, 2, order);
+  LaunchOp l{};
+  l.kind = opCopy;
+  l.dtype = (uint32_t)dtype;
+  l.nbytes = count * item_size(dtype);
+  l.nbuf = 2;
+  l.buf[0] = pair[0].buf;
+  l.buf[1] = pair[1].buf;
+  return enqueue_op(c, it->second, l, pair, 2);
 }
 
-int post_coll_locked(Context& c, uint32_t kind, int world_id, int rank, int root, void* buf, size_t count,
-                     mw_dtype dtype, void* stream, mw_handle* out) {
+inline bool rooted(uint32_t kind) { return kind == opBcast || kind == opReduce || kind == opGather || kind == opScatter; }
+
+// kind is an OpKind other than opCopy.  buf / buf2 by kind:
+//   broadcast, all-reduce, reduce: buf = the rank's tensor
+//   all-gather: buf = source (count), buf2 = destination (n x count)
+//   gather:     buf = source (count), buf2 = destination (n x count), used on the root only
+//   scatter:    buf = source (n x count), used on the root only, buf2 = destination (count)
+int post_coll_locked(Context& c, uint32_t kind, int world_id, int rank, int root, const void* buf, void* buf2,
+                     size_t count, mw_dtype dtype, void* stream, mw_handle* out) {
   if (!out || (dtype != MW_F32 && dtype != MW_BF16)) return MW_EINVAL;
   auto it = c.world_of_id.find(world_id);
   if (it == c.world_of_id.end()) return MW_ENOWORLD;
@@ -331,10 +341,16 @@ int post_coll_locked(Context& c, uint32_t kind, int world_id, int rank, int root
   const int n = (int)w.members.size();
   if (n > MW_MAX_COLL_RANKS) return MW_EINVAL;
   if (rank < 0 || rank >= n) return MW_EINVAL;
-  if (kind == kBcast && (root < 0 || root >= n)) return MW_EINVAL;
-  if (count > 0 && !buf) return MW_EINVAL;
-  if (kind == kReduce && ((uintptr_t)buf % item_size(dtype)) != 0) return MW_EINVAL;  // elements are loaded whole
-  if (count > (SIZE_MAX >> 3)) return MW_EINVAL;
+  if (rooted(kind) && (root < 0 || root >= n)) return MW_EINVAL;
+  if (!rooted(kind)) root = 0;
+  if (count > (SIZE_MAX >> 6)) return MW_EINVAL;
+  if (count > 0) {
+    const bool need1 = kind != opScatter || rank == root;
+    const bool need2 = kind == opAllGather || kind == opScatter || (kind == opGather && rank == root);
+    if ((need1 && !buf) || (need2 && !buf2)) return MW_EINVAL;
+  }
+  if ((kind == opAllReduce || kind == opReduce) && ((uintptr_t)buf % item_size(dtype)) != 0)
+    return MW_EINVAL;  // elements are loaded whole
   if (w.state == MW_BROKEN) return MW_EBROKEN;
   uint32_t hs;
   int rc = alloc_handle(c, &hs);
@@ -346,8 +362,8 @@ int post_coll_locked(Context& c, uint32_t kind, int world_id, int rank, int root
   Coll& cl = w.coll[idx];
   cl.have[rank] = true;
   cl.kind[rank] = kind;
-  cl.root[rank] = (kind == kBcast) ? root : 0;
-  cl.post[rank] = Post{hs, (uint64_t)(uintptr_t)buf, (uint64_t)count, (uint32_t)dtype, stream};
+  cl.root[rank] = root;
+  cl.post[rank] = Post{hs, (uint64_t)(uintptr_t)buf, (uint64_t)count, (uint32_t)dtype, stream, (uint64_t)(uintptr_t)buf2};
   cl.nposted += 1;
   // A world's collectives run in sequence order, each as soon as all its ranks have posted.
   while (!w.coll.empty() && w.coll.front().nposted == n) {
@@ -363,21 +379,47 @@ int post_coll_locked(Context& c, uint32_t kind, int world_id, int rank, int root
       for (int r = 0; r < n; ++r) finish_handle(c, f.post[r].hslot, MW_EMISMATCH);
       continue;
     }
-    if (f.post[0].count == 0 || n == 1) {  // nothing to move
+    const uint32_t k = f.kind[0];
+    const int rt = f.root[0];
+    const bool moves_alone = k == opAllGather || k == opGather || k == opScatter;  // a 1-rank world still copies
+    if (f.post[0].count == 0 || (n == 1 && (!moves_alone || f.post[0].buf == f.post[0].buf2))) {
       for (int r = 0; r < n; ++r) finish_handle(c, f.post[r].hslot, MW_DONE);
       continue;
     }
-    int order[kMaxBufs];
-    int k = 0;
-    if (f.kind[0] == kBcast) {  // descriptor order: root first, then the other ranks ascending
-      order[k++] = f.root[0];
-      for (int r = 0; r < n; ++r)
-        if (r != f.root[0]) order[k++] = r;
-    } else {
-      for (int r = 0; r < n; ++r) order[k++] = r;
+    LaunchOp l{};
+    l.kind = k;
+    l.dtype = f.post[0].dtype;
+    l.nbytes = f.post[0].count * item_size(f.post[0].dtype);
+    l.nbuf = (uint32_t)n;
+    l.root = (uint32_t)rt;
+    switch (k) {
+      case opBcast: {  // root first, then the other ranks ascending
+        int at = 0;
+        l.buf[at++] = f.post[rt].buf;
+        for (int r = 0; r < n; ++r)
+          if (r != rt) l.buf[at++] = f.post[r].buf;
+        break;
+      }
+      case opAllReduce:
+      case opReduce:
+        for (int r = 0; r < n; ++r) l.buf[r] = f.post[r].buf;
+        break;
+      case opAllGather:
+        for (int r = 0; r < n; ++r) {
+          l.buf[r] = f.post[r].buf;
+          l.buf[8 + r] = f.post[r].buf2;
+        }
+        break;
+      case opGather:
+        for (int r = 0; r < n; ++r) l.buf[r] = f.post[r].buf;
+        l.buf[8] = f.post[rt].buf2;
+        break;
+      default:  // opScatter
+        l.buf[0] = f.post[rt].buf;
+        for (int r = 0; r < n; ++r) l.buf[8 + r] = f.post[r].buf2;
+        break;
     }
-    rc = enqueue_op(c, it->second, f.kind[0], f.post[0].dtype, f.post[0].count * item_size(f.post[0].dtype),
-                    f.post, n, order);
+    rc = enqueue_op(c, it->second, l, f.post, n);
     if (rc != MW_OK) return rc;
   }
   return MW_OK;
@@ -390,11 +432,11 @@ int post_p2p(bool is_send, int world_id, int src, int dst, const void* buf, size
   return post_p2p_locked(*g_ctx, is_send, world_id, src, dst, buf, count, dtype, stream, out);
 }
 
-int post_coll(uint32_t kind, int world_id, int rank, int root, void* buf, size_t count, mw_dtype dtype,
-              void* stream, mw_handle* out) {
+int post_coll(uint32_t kind, int world_id, int rank, int root, const void* buf, void* buf2, size_t count,
+              mw_dtype dtype, void* stream, mw_handle* out) {
   std::lock_guard<std::mutex> g(g_lock);
   if (!g_ctx) return MW_ENOTINIT;
-  return post_coll_locked(*g_ctx, kind, world_id, rank, root, buf, count, dtype, stream, out);
+  return post_coll_locked(*g_ctx, kind, world_id, rank, root, buf, buf2, count, dtype, stream, out);
 }
 
 int abort_world_locked(Context& c, World& w) {
@@ -569,12 +611,32 @@ int mw_recv(int world_id, int src_rank, int dst_rank, void* buf, size_t count, m
 
 int mw_broadcast(int world_id, int rank, int root_rank, void* buf, size_t count, mw_dtype dtype,
                  void* hip_stream, mw_handle* out) {
-  return post_coll(kBcast, world_id, rank, root_rank, buf, count, dtype, hip_stream, out);
+  return post_coll(opBcast, world_id, rank, root_rank, buf, nullptr, count, dtype, hip_stream, out);
 }
 
 int mw_allreduce_sum(int world_id, int rank, void* buf, size_t count, mw_dtype dtype, void* hip_stream,
                      mw_handle* out) {
-  return post_coll(kReduce, world_id, rank, 0, buf, count, dtype, hip_stream, out);
+  return post_coll(opAllReduce, world_id, rank, 0, buf, nullptr, count, dtype, hip_stream, out);
+}
+
+int mw_reduce_sum(int world_id, int rank, int root_rank, void* buf, size_t count, mw_dtype dtype, void* hip_stream,
+                  mw_handle* out) {
+  return post_coll(opReduce, world_id, rank, root_rank, buf, nullptr, count, dtype, hip_stream, out);
+}
+
+int mw_all_gather(int world_id, int rank, const void* sendbuf, void* recvbuf, size_t count, mw_dtype dtype,
+                  void* hip_stream, mw_handle* out) {
+  return post_coll(opAllGather, world_id, rank, 0, sendbuf, recvbuf, count, dtype, hip_stream, out);
+}
+
+int mw_gather(int world_id, int rank, int root_rank, const void* sendbuf, void* recvbuf, size_t count,
+              mw_dtype dtype, void* hip_stream, mw_handle* out) {
+  return post_coll(opGather, world_id, rank, root_rank, sendbuf, recvbuf, count, dtype, hip_stream, out);
+}
+
+int mw_scatter(int world_id, int rank, int root_rank, const void* sendbuf, void* recvbuf, size_t count,
+               mw_dtype dtype, void* hip_stream, mw_handle* out) {
+  return post_coll(opScatter, world_id, rank, root_rank, sendbuf, recvbuf, count, dtype, hip_stream, out);
 }
 
 int mw_post_many(const mw_post_desc* posts, int n, mw_handle* handles, int* results) {
@@ -596,12 +658,28 @@ int mw_post_many(const mw_post_desc* posts, int n, mw_handle* handles, int* resu
                              p.hip_stream, &handles[i]);
         break;
       case MW_POST_BROADCAST:
-        rc = post_coll_locked(*g_ctx, kBcast, p.world_id, p.a, p.b, p.buf, (size_t)p.count, (mw_dtype)p.dtype,
-                              p.hip_stream, &handles[i]);
+        rc = post_coll_locked(*g_ctx, opBcast, p.world_id, p.a, p.b, p.buf, nullptr, (size_t)p.count,
+                              (mw_dtype)p.dtype, p.hip_stream, &handles[i]);
         break;
       case MW_POST_ALLREDUCE_SUM:
-        rc = post_coll_locked(*g_ctx, kReduce, p.world_id, p.a, 0, p.buf, (size_t)p.count, (mw_dtype)p.dtype,
-                              p.hip_stream, &handles[i]);
+        rc = post_coll_locked(*g_ctx, opAllReduce, p.world_id, p.a, 0, p.buf, nullptr, (size_t)p.count,
+                              (mw_dtype)p.dtype, p.hip_stream, &handles[i]);
+        break;
+      case MW_POST_REDUCE_SUM:
+        rc = post_coll_locked(*g_ctx, opReduce, p.world_id, p.a, p.b, p.buf, nullptr, (size_t)p.count,
+                              (mw_dtype)p.dtype, p.hip_stream, &handles[i]);
+        break;
+      case MW_POST_ALL_GATHER:
+        rc = post_coll_locked(*g_ctx, opAllGather, p.world_id, p.a, 0, p.buf, p.buf2, (size_t)p.count,
+                              (mw_dtype)p.dtype, p.hip_stream, &handles[i]);
+        break;
+      case MW_POST_GATHER:
+        rc = post_coll_locked(*g_ctx, opGather, p.world_id, p.a, p.b, p.buf, p.buf2, (size_t)p.count,
+                              (mw_dtype)p.dtype, p.hip_stream, &handles[i]);
+        break;
+      case MW_POST_SCATTER:
+        rc = post_coll_locked(*g_ctx, opScatter, p.world_id, p.a, p.b, p.buf, p.buf2, (size_t)p.count,
+                              (mw_dtype)p.dtype, p.hip_stream, &handles[i]);
         break;
       default:
         rc = MW_EINVAL;

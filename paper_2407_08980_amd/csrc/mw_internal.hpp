@@ -16,20 +16,31 @@ constexpr int kSlotBytes = 256;      // one ring slot in HBM
 constexpr int kHeaderBytes = 256;    // one ring header in HBM
 constexpr int kMaxRingDepth = 64;
 
+constexpr int kMaxOpBufs = 16;       // buffers one operation may name (all-gather: 8 sources + 8 destinations)
+
+// Kernel kinds (one internal stream and one profile counter each).
 enum Kind : uint32_t { kCopy = 0, kBcast = 1, kReduce = 2, kNumKinds = 3 };
+
+// Operation kinds.  Gather and scatter run as copy segments, all-gather as fan-out segments,
+// reduce as an all-reduce that stores to the root only.
+enum OpKind : uint32_t {
+  opCopy = 0, opBcast = 1, opAllReduce = 2, opReduce = 3, opAllGather = 4, opGather = 5, opScatter = 6, opNumKinds = 7
+};
 
 // Journal half of a ring slot (first 128 bytes): the descriptor of the operation
 // occupying the slot, written by the GPU when the operation is dispatched.
 struct SlotDesc {
-  uint64_t buf[kMaxBufs];  // copy: {src, dst}; bcast: {root, dst...}; reduce: all ranks' buffers
-  uint64_t nbytes;
-  uint32_t kind;
+  uint64_t buf[kMaxBufs];  // buffers of the operation's first kernel entry: copy {src, dst}; broadcast
+                           // {root, dst...}; (all-)reduce: all ranks; gather / scatter / all-gather: the
+                           // first segment's source and destination(s)
+  uint64_t nbytes;         // bytes per rank
+  uint32_t kind;           // OpKind
   uint32_t dtype;
   uint32_t nbuf;
   uint32_t world_id;
   uint32_t world_epoch;
   uint32_t gen;       // completion generation this operation publishes
-  uint32_t nchunks;
+  uint32_t nchunks;        // chunks of the whole operation (all its segments)
   uint32_t chunk_bytes;
   uint32_t pad[6];
 };
@@ -61,14 +72,22 @@ struct RingHeader {
 };
 static_assert(sizeof(RingHeader) == kHeaderBytes, "ring header size");
 
-// One operation handed to a launch.
+// One operation handed to a launch.  Buffer layout by kind:
+//   opCopy       buf[0] = source, buf[1] = destination                                  (nbuf = 2)
+//   opBcast      buf[0] = root's buffer, buf[1..n-1] = the other ranks' in rank order   (nbuf = n)
+//   opAllReduce  buf[r] = rank r's buffer                                               (nbuf = n)
+//   opReduce     buf[r] = rank r's buffer; only buf[root] is written                    (nbuf = n)
+//   opAllGather  buf[r] = rank r's source, buf[8 + r] = rank r's destination (n x nbytes)
+//   opGather     buf[r] = rank r's source, buf[8] = the root's destination (n x nbytes)
+//   opScatter    buf[0] = the root's source (n x nbytes), buf[8 + r] = rank r's destination
 struct LaunchOp {
-  uint64_t buf[kMaxBufs];
-  uint64_t nbytes;
-  uint32_t kind;
+  uint64_t buf[kMaxOpBufs];
+  uint64_t nbytes;  // bytes per rank
+  uint32_t kind;    // OpKind
   uint32_t dtype;
-  uint32_t nbuf;
-  uint32_t slot;   // global ring slot index
+  uint32_t nbuf;    // ranks taking part (2 for a copy)
+  uint32_t root;
+  uint32_t slot;    // global ring slot index
   uint32_t gen;
   uint32_t world_id;
   uint32_t world_epoch;

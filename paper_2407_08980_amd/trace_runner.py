@@ -115,8 +115,11 @@ def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn
         t_start = time.time()
         for idx, op in enumerate(trace.ops):
             k = op.kind
-            if k in ("send", "recv", "bcast", "allreduce"):
-                t = get(op.buf)
+            if k in ("send", "recv", "bcast", "allreduce", "reduce", "allgather", "gather", "scatter"):
+                t = get(op.buf) if op.buf >= 0 else None
+                t2 = get(op.buf2) if op.buf2 >= 0 else None
+                p1 = t.data_ptr() if t is not None else None
+                p2 = t2.data_ptr() if t2 is not None else None
                 s = streams[op.stream]
                 if touched:  # make every caller stream see the initialised bytes
                     for st in streams:
@@ -130,8 +133,16 @@ def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn
                         h = mw.mw_recv(op.world, op.a, op.b, t.data_ptr(), op.count, dt, s.cuda_stream)
                     elif k == "bcast":
                         h = mw.mw_broadcast(op.world, op.a, op.b, t.data_ptr(), op.count, dt, s.cuda_stream)
-                    else:
+                    elif k == "allreduce":
                         h = mw.mw_allreduce_sum(op.world, op.a, t.data_ptr(), op.count, dt, s.cuda_stream)
+                    elif k == "reduce":
+                        h = mw.mw_reduce_sum(op.world, op.a, op.b, p1, op.count, dt, s.cuda_stream)
+                    elif k == "allgather":
+                        h = mw.mw_all_gather(op.world, op.a, p1, p2, op.count, dt, s.cuda_stream)
+                    elif k == "gather":
+                        h = mw.mw_gather(op.world, op.a, op.b, p1, p2, op.count, dt, s.cuda_stream)
+                    else:
+                        h = mw.mw_scatter(op.world, op.a, op.b, p1, p2, op.count, dt, s.cuda_stream)
                     outstanding.append((idx, h))
                 except mw.MwError as e:
                     if e.code != mw.MW_EBROKEN:
@@ -174,7 +185,7 @@ def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn
                 out.world_state[op.world] = "alive" if mw.mw_world_state(op.world) == mw.MW_ALIVE else "broken"
         for idx, st in out.status.items():
             o = trace.ops[idx]
-            if st == "done" and (o.kind == "recv" or (o.kind in ("bcast", "allreduce") and o.a == 0)):
+            if st == "done" and (o.kind == "recv" or (o.kind not in ("send", "recv") and o.a == 0)):
                 out.payload_bytes_done += o.count * ITEMSIZE[o.dtype]
     finally:
         mw.mw_shutdown()

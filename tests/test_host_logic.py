@@ -38,10 +38,10 @@ def ctx(hostlib):
 
 
 def log_entry(lib, i):
-    out = (C.c_uint64 * 17)()
+    out = (C.c_uint64 * 26)()
     assert lib.mwt_log_entry(i, out) == 0
     return dict(buf=list(out[:8]), nbytes=out[8], kind=out[9], dtype=out[10], nbuf=out[11], slot=out[12],
-                gen=out[13], world=out[14], epoch=out[15], launch=out[16])
+                gen=out[13], world=out[14], epoch=out[15], launch=out[16], root=out[17], buf_hi=list(out[18:26]))
 
 
 def test_header_symbols_are_exported_by_the_product_library():
@@ -340,3 +340,65 @@ def test_many_worlds_lookup_is_by_key(ctx):
         w & 0xFFFFFFFF for w in ids)
     ctx.mwt_complete(5, 1)  # completion order is irrelevant
     assert [mw.mw_poll(h) for h in hs] == [mw.MW_DONE] * 5
+
+
+def test_rooted_and_gathering_collectives_descriptors(ctx):
+    mw.mw_world_create(0, [0, 1, 2])
+    n, S = 3, 40
+    # reduce: all ranks' buffers in rank order, root recorded
+    h = [mw.mw_reduce_sum(0, r, 2, 0x100 * (r + 1), 10, mw.MW_F32) for r in (1, 2, 0)]
+    # all-gather: sources in 0..n-1, destinations in 8..8+n-1
+    h += [mw.mw_all_gather(0, r, 0x1000 + r, 0x2000 + 0x100 * r, 20, mw.MW_BF16) for r in range(n)]
+    # gather to root 1 / scatter from root 0: NULL where the buffer is unused
+    h += [mw.mw_gather(0, r, 1, 0x3000 + r, 0x4000 if r == 1 else None, 10, mw.MW_F32) for r in range(n)]
+    h += [mw.mw_scatter(0, r, 0, 0x5000 if r == 0 else None, 0x6000 + 0x100 * r, 10, mw.MW_F32) for r in range(n)]
+    mw.mw_flush()
+    assert ctx.mwt_log_size() == 4 and ctx.mwt_launch_size(0) == 4
+    red, ag, ga, sc = (log_entry(ctx, i) for i in range(4))
+    assert (red["kind"], red["nbuf"], red["root"], red["buf"][:3], red["nbytes"]) == (3, 3, 2, [0x100, 0x200, 0x300], S)
+    assert (ag["kind"], ag["buf"][:3], ag["buf_hi"][:3]) == (4, [0x1000, 0x1001, 0x1002], [0x2000, 0x2100, 0x2200])
+    assert (ga["kind"], ga["root"], ga["buf"][:3], ga["buf_hi"][0], ga["nbytes"]) == (5, 1, [0x3000, 0x3001, 0x3002], 0x4000, S)
+    assert (sc["kind"], sc["root"], sc["buf"][0], sc["buf_hi"][:3]) == (6, 0, 0x5000, [0x6000, 0x6100, 0x6200])
+    ctx.mwt_complete(4, 0)
+    assert [mw.mw_poll(x) for x in h] == [mw.MW_DONE] * 12
+    # argument checks: the root needs its receive / send buffer; roots and kinds must agree
+    with pytest.raises(mw.MwError) as e:
+        mw.mw_gather(0, 1, 1, 0x3000, None, 10, mw.MW_F32)
+    assert e.value.code == mw.MW_EINVAL
+    with pytest.raises(mw.MwError) as e:
+        mw.mw_scatter(0, 0, 0, None, 0x6000, 10, mw.MW_F32)
+    assert e.value.code == mw.MW_EINVAL
+    with pytest.raises(mw.MwError) as e:
+        mw.mw_reduce_sum(0, 0, 3, 0x100, 10, mw.MW_F32)
+    assert e.value.code == mw.MW_EINVAL
+    a = mw.mw_reduce_sum(0, 0, 1, 0x100, 10, mw.MW_F32)
+    b = mw.mw_reduce_sum(0, 1, 2, 0x200, 10, mw.MW_F32)
+    c = mw.mw_allreduce_sum(0, 2, 0x300, 10, mw.MW_F32)
+    assert [mw.mw_poll(x) for x in (a, b, c)] == [mw.MW_EMISMATCH] * 3
+    # a one-rank world: gathering into place is nothing to do, otherwise it is a copy
+    mw.mw_world_create(1, [5])
+    assert mw.mw_poll(mw.mw_all_gather(1, 0, 0x7000, 0x7000, 4, mw.MW_F32)) == mw.MW_DONE
+    hcopy = mw.mw_gather(1, 0, 0, 0x7000, 0x8000, 4, mw.MW_F32)
+    assert mw.mw_poll(hcopy) == mw.MW_PENDING and log_entry(ctx, 4)["kind"] == 5
+    ctx.mwt_complete(1, 0)
+    assert mw.mw_poll(hcopy) == mw.MW_DONE
+
+
+def test_post_many_mixed_batch(ctx):
+    mw.mw_world_create(0, [0, 1])
+    mw.mw_world_create(1, [2, 3])
+    mw.mw_world_abort(1)
+    handles, results = mw.mw_post_many([
+        (mw.POST_SEND, 0, 0, 1, 0x10, 4, mw.MW_F32, mw.STREAM_NONE),
+        (mw.POST_RECV, 0, 0, 1, 0x20, 4, mw.MW_F32, mw.STREAM_NONE),
+        (mw.POST_SEND, 1, 0, 1, 0x10, 4, mw.MW_F32, mw.STREAM_NONE),          # broken world: refused
+        (mw.POST_ALL_GATHER, 0, 0, 0, 0x30, 4, mw.MW_F32, mw.STREAM_NONE, 0x40),
+        (mw.POST_ALL_GATHER, 0, 1, 0, 0x50, 4, mw.MW_F32, mw.STREAM_NONE, 0x60),
+        (99, 0, 0, 1, 0x10, 4, mw.MW_F32, mw.STREAM_NONE),                      # unknown kind
+    ])
+    assert results == [0, 0, mw.MW_EBROKEN, 0, 0, mw.MW_EINVAL]
+    assert handles[2] == 0 and handles[5] == 0 and all(handles[i] for i in (0, 1, 3, 4))
+    mw.mw_flush()
+    assert ctx.mwt_launch_size(0) == 2
+    ctx.mwt_complete(2, 0)
+    assert [mw.mw_poll(handles[i]) for i in (0, 1, 3, 4)] == [mw.MW_DONE] * 4

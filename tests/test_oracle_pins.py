@@ -483,3 +483,91 @@ def test_pending_recv_in_one_world_never_blocks_another():
         o.post_recv(1, 1, 0, dst, 2, F32)
         assert o.status(o.post_send(1, 1, 0, src, 2, F32)) == DONE and np.array_equal(dst, src)
         assert o.status(stuck) == PENDING
+
+
+# ---------------------------------------------------------------------------
+# reduce / all-gather / gather / scatter (the communicator's other four operations)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n", [2, 3, 4])
+def test_reduce_leaves_the_exact_sum_on_the_root_only(n):
+    rng = np.random.default_rng(40 + n)
+    for root in range(n):
+        xs = [rng.standard_normal(12).astype(np.float32) for _ in range(n)]
+        o = WorldOracle(n)
+        o.create(0, tuple(range(n)))
+        bufs = [u8(x).copy() for x in xs]
+        hs = [o.post_reduce(0, r, root, bufs[r], 12, F32) for r in range(n)]
+        assert all(o.status(h) == DONE for h in hs)
+        s, sabs = o.reduce_ref[hs[root]]
+        for i in range(12):
+            exact = sum(Fraction(float(x[i])) for x in xs)
+            exact_abs = sum(abs(Fraction(float(x[i]))) for x in xs)
+            assert abs(Fraction(float(s[i])) - exact) <= exact_abs * Fraction(n, 2 ** 52)
+        assert np.array_equal(bufs[root].view(np.float32), s.astype(np.float32))
+        for r in range(n):
+            if r != root:
+                assert np.array_equal(bufs[r], u8(xs[r])) and hs[r] not in o.reduce_ref
+    # integer inputs: exact, equal to python's integer sum
+    ints = [np.arange(-8, 8) * (r + 1) for r in range(3)]
+    o = WorldOracle(3)
+    o.create(0, (0, 1, 2))
+    bufs = [u8(v.astype(np.float32)).copy() for v in ints]
+    for r in range(3):
+        o.post_reduce(0, r, 2, bufs[r], 16, F32)
+    assert [int(v) for v in bufs[2].view(np.float32)] == [sum(int(v[i]) for v in ints) for i in range(16)]
+
+
+@pytest.mark.parametrize("n", [2, 3, 4])
+def test_all_gather_gather_scatter_brute_force(n):
+    count = 5
+    send = [rand_bytes(count * 2, 60 + 10 * n + r) for r in range(n)]
+    # all-gather: byte j of rank q's tensor lands at q*S + j on every rank
+    o = WorldOracle(n)
+    o.create(0, tuple(range(n)))
+    recv = [np.full(n * count * 2 + 3, 0xA5, np.uint8) for _ in range(n)]
+    keep = [s.copy() for s in send]
+    hs = [o.post_all_gather(0, r, send[r], recv[r], count, BF16) for r in reversed(range(n))]
+    assert all(o.status(h) == DONE for h in hs)
+    for r in range(n):
+        for q in range(n):
+            for j in range(count * 2):
+                assert recv[r][q * count * 2 + j] == keep[q][j]
+        assert np.all(recv[r][n * count * 2:] == 0xA5) and np.array_equal(send[r], keep[r])
+    for root in range(n):
+        # gather: the same concatenation, on the root only
+        o = WorldOracle(n)
+        o.create(0, tuple(range(n)))
+        groot = np.full(n * count * 2, 0xA5, np.uint8)
+        hs = [o.post_gather(0, r, root, send[r], groot if r == root else None, count, BF16) for r in range(n)]
+        assert all(o.status(h) == DONE for h in hs)
+        assert np.array_equal(groot, recv[0][: n * count * 2])
+        # scatter undoes gather: rank r gets back its own tensor
+        back = [np.full(count * 2, 0xA5, np.uint8) for _ in range(n)]
+        hs = [o.post_scatter(0, r, root, groot if r == root else None, back[r], count, BF16) for r in range(n)]
+        assert all(o.status(h) == DONE for h in hs)
+        for r in range(n):
+            assert np.array_equal(back[r], keep[r])
+            for j in range(count * 2):
+                assert oracle.scatter_result(groot, n, r)[j] == groot[r * count * 2 + j]
+
+
+def test_all_gather_in_place_and_rooted_mismatch():
+    n, count = 3, 4
+    o = WorldOracle(n)
+    o.create(0, (0, 1, 2))
+    recv = [rand_bytes(n * count * 4, 90 + r) for r in range(n)]
+    mine = [recv[r][r * count * 4 : (r + 1) * count * 4].copy() for r in range(n)]
+    # each rank's contribution already sits in its own slot of its receive buffer
+    hs = [o.post_all_gather(0, r, recv[r][r * count * 4 : (r + 1) * count * 4], recv[r], count, F32) for r in range(n)]
+    assert all(o.status(h) == DONE for h in hs)
+    for r in range(n):
+        assert np.array_equal(recv[r], np.concatenate(mine))
+    b = [rand_bytes(16, r) for r in range(n)]
+    hs = [o.post_reduce(0, r, r % 2, b[r], 4, F32) for r in range(n)]  # roots disagree
+    assert all(o.status(h) == MISMATCH for h in hs)
+    hs = [o.post_gather(0, 0, 0, b[0], np.zeros(48, np.uint8), 4, F32), o.post_scatter(0, 1, 0, None, b[1], 4, F32),
+          o.post_gather(0, 2, 0, b[2], None, 4, F32)]  # kinds disagree
+    assert all(o.status(h) == MISMATCH for h in hs)
+    pend = o.post_all_gather(0, 0, b[0], np.zeros(48, np.uint8), 4, F32)
+    o.abort_world(0)
+    assert o.status(pend) == BROKEN

@@ -14,5 +14,6 @@ from .configs import (  # noqa: F401
     config3,
     config4,
     config5,
+    collectives_mix,
     single_world_of,
 )

@@ -302,6 +302,96 @@ def config5(n_ops=10_000, n_worlds=64, n_workers=32, min_bytes=4096, max_bytes=1
 
 
 # ---------------------------------------------------------------------------
+# all eight operations of the communicator, mixed
+# ---------------------------------------------------------------------------
+def collectives_mix(n_ops=400, n_worlds=12, n_workers=16, min_bytes=64, max_bytes=1 << 20, window=24, n_aborts=2,
+                    max_ranks=4, seed_offset=6):
+    """Worlds of 2..max_ranks members; every op is one of send-recv, broadcast, all-reduce, reduce,
+    all-gather, gather, scatter (uniformly), fp32 or bf16, log-uniform size, seeded posting order;
+    n_aborts workers are aborted at seeded positions.  Every op uses fresh buffers and is checked."""
+    t = Trace("collectives_mix", n_workers=n_workers, n_streams=3)
+    sd = _Seeds(seed_offset)
+    rng = sd.rng
+    members = []
+    for w in range(n_worlds):
+        size = int(rng.integers(2, max_ranks + 1))
+        m = tuple(int(x) for x in rng.choice(n_workers, size=size, replace=False))
+        members.append(m)
+        t.create(w, m)
+    abort_at = {}
+    for v in rng.choice(n_workers, size=n_aborts, replace=False):
+        abort_at.setdefault(int(rng.integers(n_ops // 3, n_ops)), []).append(int(v))
+    live = []
+    lo, hi = math.log(min_bytes), math.log(max_bytes)
+    kinds = ["p2p", "bcast", "allreduce", "reduce", "allgather", "gather", "scatter"]
+
+    def close_window():
+        t.wait()
+        for bufs in live:
+            for b in bufs:
+                t.check(b)
+        for bufs in live:
+            for b in bufs:
+                t.free(b)
+        live.clear()
+
+    for i in range(n_ops):
+        for v in abort_at.get(i, ()):
+            t.abort_worker(v)
+        w = int(rng.integers(0, n_worlds))
+        n = len(members[w])
+        kind = kinds[int(rng.integers(0, len(kinds)))]
+        dtype = "f32" if rng.integers(0, 2) == 0 else "bf16"
+        isz = ITEMSIZE[dtype]
+        count = max(1, int(math.exp(rng.uniform(lo, hi))) // isz)
+        stream = int(rng.integers(0, t.n_streams))
+        order = [int(x) for x in rng.permutation(n)]
+        root = int(rng.integers(0, n))
+        draw = lambda c: t.tensor(c, dtype, ("uniform", dtype, sd.next()))
+        poison = lambda c: t.tensor(c, dtype, ("fill", POISON))
+        bufs = []
+        if kind == "p2p":
+            src, dst = (int(x) for x in rng.choice(n, size=2, replace=False))
+            sb, db = draw(count), poison(count)
+            bufs = [sb, db]
+            t.recv(w, src, dst, db, count, dtype, stream)
+            t.send(w, src, dst, sb, count, dtype, stream)
+        elif kind in ("bcast", "allreduce", "reduce"):
+            bufs = [draw(count) if (kind != "bcast" or r == root) else poison(count) for r in range(n)]
+            for r in order:
+                if kind == "bcast":
+                    t.bcast(w, r, root, bufs[r], count, dtype, stream)
+                elif kind == "allreduce":
+                    t.allreduce(w, r, bufs[r], count, dtype, stream)
+                else:
+                    t.reduce(w, r, root, bufs[r], count, dtype, stream)
+        elif kind == "allgather":
+            sends = [draw(count) for _ in range(n)]
+            recvs = [poison(n * count) for _ in range(n)]
+            bufs = sends + recvs
+            for r in order:
+                t.allgather(w, r, sends[r], recvs[r], count, dtype, stream)
+        elif kind == "gather":
+            sends = [draw(count) for _ in range(n)]
+            recv = poison(n * count)
+            bufs = sends + [recv]
+            for r in order:
+                t.gather(w, r, root, sends[r], recv if r == root else -1, count, dtype, stream)
+        else:
+            send = draw(n * count)
+            recvs = [poison(count) for _ in range(n)]
+            bufs = [send] + recvs
+            for r in order:
+                t.scatter(w, r, root, send if r == root else -1, recvs[r], count, dtype, stream)
+        live.append(bufs)
+        if len(live) == window:
+            close_window()
+    close_window()
+    t.meta.update(members=members, abort_at=abort_at, n_ops=n_ops)
+    return t
+
+
+# ---------------------------------------------------------------------------
 # single-world baseline of a point-to-point trace
 # ---------------------------------------------------------------------------
 def single_world_of(trace, drop_aborts=True):
@@ -319,7 +409,7 @@ def single_world_of(trace, drop_aborts=True):
         elif op.kind in ("send", "recv"):
             m = members[op.world]
             out.add(Op(op.kind, 0, m[op.a], m[op.b], op.buf, op.count, op.dtype, op.stream))
-        elif op.kind in ("bcast", "allreduce"):
+        elif op.kind in ("bcast", "allreduce", "reduce", "allgather", "gather", "scatter"):
             raise ValueError("single_world_of maps point-to-point traces only")
         elif op.kind == "abort_worker":
             if not drop_aborts:

@@ -16,7 +16,7 @@ from dataclasses import dataclass, field
 
 from .data import ITEMSIZE, BufSpec
 
-POSTING = ("send", "recv", "bcast", "allreduce")
+POSTING = ("send", "recv", "bcast", "allreduce", "reduce", "allgather", "gather", "scatter")
 
 
 @dataclass
@@ -30,6 +30,7 @@ class Op:
     dtype: str = "f32"
     stream: int = 0  # which of the runner's caller-side streams the post is ordered after
     members: tuple = ()
+    buf2: int = -1  # allgather / gather: receive buffer; scatter: receive buffer (buf is then the root's source)
 
 
 @dataclass
@@ -69,6 +70,20 @@ class Trace:
     def allreduce(self, world, rank, buf, count, dtype, stream=0):
         return self.add(Op("allreduce", world, rank, -1, buf, count, dtype, stream))
 
+    def reduce(self, world, rank, root, buf, count, dtype, stream=0):
+        return self.add(Op("reduce", world, rank, root, buf, count, dtype, stream))
+
+    def allgather(self, world, rank, sendbuf, recvbuf, count, dtype, stream=0):
+        return self.add(Op("allgather", world, rank, -1, sendbuf, count, dtype, stream, (), recvbuf))
+
+    def gather(self, world, rank, root, sendbuf, recvbuf, count, dtype, stream=0):
+        """recvbuf is -1 on every rank but the root."""
+        return self.add(Op("gather", world, rank, root, sendbuf, count, dtype, stream, (), recvbuf))
+
+    def scatter(self, world, rank, root, sendbuf, recvbuf, count, dtype, stream=0):
+        """sendbuf is -1 on every rank but the root."""
+        return self.add(Op("scatter", world, rank, root, sendbuf, count, dtype, stream, (), recvbuf))
+
     def abort_world(self, world):
         return self.add(Op("abort_world", world=world))
 
@@ -96,6 +111,6 @@ class Trace:
         per collective (counted once on its rank-0 post)."""
         total = 0
         for op in self.ops:
-            if op.kind == "recv" or (op.kind in ("bcast", "allreduce") and op.a == 0):
+            if op.kind == "recv" or (op.kind in POSTING[2:] and op.a == 0):
                 total += op.count * ITEMSIZE[op.dtype]
         return total
