@@ -45,7 +45,7 @@ def parse():
     ap.add_argument("--calibrate", type=int, default=0,
                     help="also run this many plain 1 GiB device copies (torch copy_) before the timed region: the "
                          "known-size kernel that hardware counters of a profiling run are scaled by")
-    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "config5", "collectives"], default="config2",
+    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "config5", "collectives", "sweep", "online"], default="config2",
                     help="config2 (default) is the headline workload; the others are measured the same way")
     ap.add_argument("--abort-step", type=int, default=100, help="config4: step before which worker 7 is aborted")
     ap.add_argument("--ops", type=int, default=10_000, help="config5: operations in the trace")
@@ -721,6 +721,171 @@ def run_collectives(torch, mw, dev, reps):
     }
 
 
+def run_sweep(torch, mw, dev, reps):
+    """The paper's multi-sender experiment in shape (Sec. 4.3): 1-3 senders -> one receiver, fp32 tensors of
+    1 000 / 10 000 / 100 000 / 1 000 000 elements (4 KB ... 4 MB), single world (SW: one world holding the
+    receiver and all senders) against MultiWorld (MW: one world per sender, the receiver in all of them).
+    Receiver-side throughput over 128 windows of 16 messages per sender; same harness, same kernels."""
+    sizes = [1_000, 10_000, 100_000, 1_000_000]
+    window, n_windows = 16, 128  # 3 senders x 16 x 2 windows in flight stays within one world's ring
+    wid = [0]
+    out = {}
+    worst = 0.0
+    for count in sizes:
+        src = [[torch.randn(count, device=dev) for _ in range(window)] for _ in range(3)]
+        dst = [[torch.zeros(count, device=dev) for _ in range(window)] for _ in range(3)]
+        torch.cuda.synchronize()
+        for senders in (1, 2, 3):
+            wid[0] += 10
+            base = wid[0]
+            for k in range(senders):
+                mw.mw_world_create(base + k, [0, 1 + k])  # MW: world k = (receiver, sender k)
+            mw.mw_world_create(base + 5, list(range(senders + 1)))  # SW: one world, receiver is rank 0
+
+            def batch(multi):
+                posts = []
+                for j in range(window):
+                    for k in range(senders):
+                        w, a = (base + k, 1) if multi else (base + 5, 1 + k)
+                        posts.append((mw.POST_RECV, w, a, 0, dst[k][j].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE))
+                        posts.append((mw.POST_SEND, w, a, 0, src[k][j].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE))
+                return mw.PostBatch(posts)
+
+            def run(pb):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                prev = None
+                for _ in range(n_windows):
+                    pb.post()
+                    mw.mw_flush()
+                    cur = mw.PollSet(list(pb.handles))
+                    if prev is not None:
+                        while prev.poll():
+                            pass
+                    prev = cur
+                while prev.poll():
+                    pass
+                return time.perf_counter() - t0
+
+            pbm, pbs = batch(True), batch(False)
+            run(pbm), run(pbs)
+            tm, ts = [], []
+            for _ in range(max(reps, 1) * 2):
+                ts.append(run(pbs))
+                tm.append(run(pbm))
+            for k in range(senders):
+                if not torch.equal(torch.stack(dst[k]), torch.stack(src[k])):
+                    raise RuntimeError("sweep: destination differs from source")
+                for d in dst[k]:
+                    d.zero_()
+            nbytes = n_windows * window * senders * count * 4
+            gm, gs = nbytes / (sum(tm) / len(tm)) / 1e9, nbytes / (sum(ts) / len(ts)) / 1e9
+            loss = (1 - gm / gs) * 100
+            worst = max(worst, loss)
+            out[f"{count * 4} B x {senders} sender(s)"] = {"MW_GBps": round(gm, 2), "SW_GBps": round(gs, 2),
+                                                          "loss_pct": round(loss, 2)}
+    big = out["4000000 B x 3 sender(s)"]
+    return {
+        "value": big["MW_GBps"], "ms_per_step": 0.0, "steps": n_windows,
+        "config": {"workload": "paper-shaped sweep: 1-3 senders -> 1 receiver, fp32 tensors of 4 KB / 40 KB / 400 KB / 4 MB, "
+                               "single world vs one world per sender, 128 windows of 16 messages per sender",
+                   "payload_dtype": "f32"},
+        "sweep": out, "worst_loss_pct": round(worst, 2), "roofline": None,
+    }
+
+
+def run_online(torch, mw, dev, reps):
+    """Online instantiation under load (Sec. 4.2 in shape): a leader receives 4 MB fp32 tensors from one worker
+    through W1; while that traffic runs, W2 is created (its latency is measured) and a second worker starts
+    sending through it; later that worker is aborted.  Receiver-side throughput is reported per window of
+    5 000 tensors per sender, as the paper does, with the library's watchdog thread running throughout."""
+    count, window, per_point = 1_000_000, 50, 5_000
+    src = [[torch.randn(count, device=dev) for _ in range(window)] for _ in range(2)]
+    dst = [[torch.zeros(count, device=dev) for _ in range(window)] for _ in range(2)]
+    torch.cuda.synchronize()
+    mw.mw_world_create(1, [0, 1])
+    mw.mw_watchdog_start(3.0, 0.1)
+
+    def batch(worlds):
+        posts = []
+        for j in range(window):
+            for k, w in enumerate(worlds):
+                posts.append((mw.POST_RECV, w, 1, 0, dst[k][j].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE))
+                posts.append((mw.POST_SEND, w, 1, 0, src[k][j].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE))
+        return mw.PostBatch(posts)
+
+    def run(pb, n_batches, beat):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        prev = None
+        for _ in range(n_batches):
+            for k in beat:
+                mw.mw_heartbeat(k)
+            pb.post(check=False)
+            mw.mw_flush()
+            cur = mw.PollSet([h for h in pb.handles if h])
+            if prev is not None and prev.n:
+                while prev.poll():
+                    pass
+            prev = cur
+        if prev.n:
+            while prev.poll():
+                pass
+        return time.perf_counter() - t0
+
+    nb = per_point // window
+    one = batch([1])
+    run(one, 10, (0, 1))
+    points = []
+    for _ in range(3):  # W1 alone
+        t = run(one, nb, (0, 1))
+        points.append({"phase": "W1 only", "W1_GBps": round(per_point * count * 4 / t / 1e9, 1)})
+    # join: create W2 while W1's last windows are still in flight
+    one.post()
+    mw.mw_flush()
+    inflight = mw.PollSet(list(one.handles))
+    joins = []
+    t0 = time.perf_counter()
+    mw.mw_world_create(2, [0, 2])
+    joins.append(time.perf_counter() - t0)
+    still_running = inflight.poll() > 0
+    while inflight.poll():
+        pass
+    for i in range(20):  # more joins, for a distribution (worlds of other worker pairs)
+        one.post()
+        mw.mw_flush()
+        inflight = mw.PollSet(list(one.handles))
+        t0 = time.perf_counter()
+        mw.mw_world_create(100 + i, [3 + i, 30 + i])
+        joins.append(time.perf_counter() - t0)
+        while inflight.poll():
+            pass
+    two = batch([1, 2])
+    for _ in range(3):  # both worlds
+        t = run(two, nb, (0, 1, 2))
+        g = round(per_point * count * 4 / t / 1e9, 1)
+        points.append({"phase": "W1 + W2", "W1_GBps": g, "W2_GBps": g})
+    mw.mw_worker_abort(2)  # the second worker leaves; W1 goes on (the same batch: W2's posts are refused)
+    for _ in range(3):
+        t = run(two, nb, (0, 1))
+        points.append({"phase": "W2 aborted", "W1_GBps": round(per_point * count * 4 / t / 1e9, 1)})
+    if not torch.equal(torch.stack(dst[0]), torch.stack(src[0])):
+        raise RuntimeError("online: destination differs from source")
+    mw.mw_watchdog_stop()
+    first_join = joins[0]
+    joins.sort()
+    return {
+        "value": points[2]["W1_GBps"], "ms_per_step": 0.0, "steps": nb,
+        "config": {"workload": "online instantiation under load: leader <- worker through W1 with 4 MB fp32 tensors, W2 "
+                               "created and a second worker joining while W1 streams, then aborted; throughput per "
+                               "5 000 tensors per sender; watchdog thread running", "payload_dtype": "f32"},
+        "points": points,
+        "world_create_latency_us": {"first_join_while_streaming": round(first_join * 1e6, 1),
+                                    "median": round(joins[len(joins) // 2] * 1e6, 1), "max": round(joins[-1] * 1e6, 1)},
+        "w1_still_in_flight_at_join": bool(still_running), "roofline": None,
+    }
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -749,6 +914,10 @@ def main():
         res = run_config1(torch, mw, dev, args.reps)
     elif args.workload == "collectives":
         res = run_collectives(torch, mw, dev, args.reps)
+    elif args.workload == "sweep":
+        res = run_sweep(torch, mw, dev, args.reps)
+    elif args.workload == "online":
+        res = run_online(torch, mw, dev, args.reps)
     else:
         res = run_config5(torch, mw, dev, args.ops, args.reps)
     mw.mw_shutdown()

@@ -158,6 +158,34 @@ int mw_scatter(int world_id, int rank, int root_rank, const void* sendbuf, void*
  * reused (at least mw_handle_capacity() further posts). */
 int mw_poll(mw_handle h);
 
+/* ---- watchdog (Sec. 3.3 "Watchdog") ------------------------------------------------------------ */
+
+/* Failures of workers that share a host are silent (Sec. 3.2 "Reliable fault detection"), so each
+ * worker reports its health periodically and a watchdog declares a worker failed when its reports
+ * have been missing for longer than a timeout ("e.g., 3 seconds"); the worlds containing it are then
+ * aborted exactly as by mw_worker_abort, and no others.
+ *
+ * mw_heartbeat(worker): the worker is alive now (steady clock).  A worker is watched from its first
+ *   heartbeat on; workers that never send one are never declared failed.  MW_EBROKEN once the worker
+ *   has been declared failed (a failed worker does not come back: recovery uses a new worker id and
+ *   new worlds, Sec. 3.1); mw_world_create refuses such a worker with MW_EBROKEN too.
+ * mw_watchdog_start(timeout_s, period_s): start the library's watchdog thread, which inspects the
+ *   heartbeat table every period_s seconds.  MW_EINVAL if it is already running.
+ * mw_watchdog_stop(): stop and join it (mw_shutdown does this too).
+ * mw_heartbeat_at / mw_watchdog_check_at: the same with the caller's clock (seconds, any origin) instead
+ *   of the steady clock and the thread: one inspection at time t with the given timeout; returns the
+ *   number of workers newly declared failed.  For callers that drive the check from their own polling
+ *   loop, and for deterministic tests.
+ * mw_worker_state: MW_ALIVE or MW_BROKEN (declared failed by the watchdog).
+ * mw_heartbeat_epoch: heartbeats received from the worker so far. */
+int mw_heartbeat(int worker_id);
+int mw_heartbeat_at(int worker_id, double t);
+int mw_watchdog_start(double timeout_s, double period_s);
+int mw_watchdog_stop(void);
+int mw_watchdog_check_at(double t, double timeout_s);
+int mw_worker_state(int worker_id);
+long mw_heartbeat_epoch(int worker_id);
+
 /* ---- extensions ----------------------------------------------------------------------------- */
 
 /* Launch every operation whose sides have all been posted (one batched launch per kernel kind,
@@ -199,7 +227,7 @@ int mw_pending_ops(void);
 int mw_poll_many(const mw_handle* handles, int n, int* states);
 
 /* Tunables, to be set between mw_init and the first post.  key: "chunk_bytes" (power of two,
- * 4096..4194304; 0 = choose per launch), "ring_depth" (1..64 slots per world), "reduce_lds"
+ * 4096..4194304; 0 = choose per launch), "ring_depth" (1..256 slots per world, default 128; before mw_init), "reduce_lds"
  * (0/1: stage all-reduce tiles through LDS).  MW_EINVAL for unknown keys or bad values. */
 int mw_config_set(const char* key, long value);
 long mw_config_get(const char* key);

@@ -62,7 +62,7 @@ ALIVE = "alive"
 
 
 class OracleError(Exception):
-    """Argument errors; .code is one of EINVAL, ENOWORLD, EEXIST."""
+    """Argument errors; .code is one of EINVAL, ENOWORLD, EEXIST, EBROKEN."""
 
     def __init__(self, code, msg=""):
         super().__init__(f"{code}: {msg}")
@@ -228,6 +228,8 @@ class WorldOracle:
         self.worlds = {}
         self.result = []  # handle -> DONE / PENDING / BROKEN / MISMATCH
         self.reduce_ref = {}  # handle -> (s, sabs) of a DONE all-reduce
+        self.last_beat = {}  # worker -> time of its latest heartbeat (workers that ever sent one)
+        self.dead = set()  # workers the watchdog has declared failed
 
     # -- world manager (Sec. 3.3 "World Manager": initialize_world) ---------
     def create(self, world, members):
@@ -238,6 +240,8 @@ class WorldOracle:
             raise OracleError("EINVAL", "members must be distinct")
         if any(m < 0 or m >= self.n_workers for m in members):
             raise OracleError("EINVAL", "worker id out of range")
+        if any(m in self.dead for m in members):
+            raise OracleError("EBROKEN", "a member has been declared failed")
         self.worlds[world] = _World(members)
 
     def world_state(self, world):
@@ -413,6 +417,24 @@ class WorldOracle:
             for post in slot.values():
                 self.result[post[0]] = BROKEN
         w.coll.clear()
+
+    # -- watchdog (Sec. 3.3 "Watchdog"): workers report their health periodically; one whose
+    #    reports have been missing for longer than the timeout is taken to have failed, and the
+    #    worlds it belongs to are cleaned up.  Time is an explicit argument here.
+    def heartbeat(self, worker, t):
+        if not (0 <= worker < self.n_workers):
+            raise OracleError("EINVAL", "worker id out of range")
+        if worker in self.dead:
+            raise OracleError("EBROKEN", "worker has been declared failed")
+        self.last_beat[worker] = max(t, self.last_beat.get(worker, t))
+
+    def watchdog_check(self, t, timeout):
+        """One inspection at time t: returns the workers newly declared failed (ascending)."""
+        late = sorted(k for k, tb in self.last_beat.items() if k not in self.dead and t - tb > timeout)
+        for k in late:
+            self.dead.add(k)
+            self.abort_worker(k)
+        return late
 
     def abort_worker(self, worker):
         if not (0 <= worker < self.n_workers):

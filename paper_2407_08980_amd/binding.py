@@ -29,7 +29,9 @@ SYMBOLS = [
     "mw_send", "mw_recv", "mw_broadcast", "mw_allreduce_sum", "mw_reduce_sum", "mw_all_gather", "mw_gather",
     "mw_scatter", "mw_poll", "mw_flush", "mw_pending_ops", "mw_poll_many", "mw_post_many",
     "mw_config_set", "mw_config_get", "mw_handle_capacity", "mw_last_hip_error", "mw_strerror",
-    "mw_profile_enable", "mw_profile_read", "mw_debug_ring_read", "mw_debug_arena_hash",
+    "mw_profile_enable", "mw_profile_read", "mw_debug_ring_read", "mw_debug_arena_hash", "mw_heartbeat",
+    "mw_heartbeat_at", "mw_watchdog_start", "mw_watchdog_stop", "mw_watchdog_check_at", "mw_worker_state",
+    "mw_heartbeat_epoch",
 ]
 
 
@@ -86,6 +88,14 @@ def declare(lib):
     lib.mw_debug_ring_read.argtypes = [i, vp, sz]
     lib.mw_debug_ring_read.restype = C.c_long
     lib.mw_debug_arena_hash.argtypes = [i, u64p]
+    lib.mw_heartbeat.argtypes = [i]
+    lib.mw_heartbeat_at.argtypes = [i, C.c_double]
+    lib.mw_watchdog_start.argtypes = [C.c_double, C.c_double]
+    lib.mw_watchdog_stop.argtypes = []
+    lib.mw_watchdog_check_at.argtypes = [C.c_double, C.c_double]
+    lib.mw_worker_state.argtypes = [i]
+    lib.mw_heartbeat_epoch.argtypes = [i]
+    lib.mw_heartbeat_epoch.restype = C.c_long
     return lib
 
 
@@ -273,6 +283,35 @@ def mw_strerror(code):
     return strerror(code)
 
 
+def mw_heartbeat(worker_id):
+    return _ck(lib().mw_heartbeat(worker_id), "mw_heartbeat")
+
+
+def mw_heartbeat_at(worker_id, t):
+    return _ck(lib().mw_heartbeat_at(worker_id, t), "mw_heartbeat_at")
+
+
+def mw_watchdog_start(timeout_s, period_s):
+    return _ck(lib().mw_watchdog_start(timeout_s, period_s), "mw_watchdog_start")
+
+
+def mw_watchdog_stop():
+    return _ck(lib().mw_watchdog_stop(), "mw_watchdog_stop")
+
+
+def mw_watchdog_check_at(t, timeout_s):
+    """Number of workers newly declared failed by this inspection."""
+    return _ck(lib().mw_watchdog_check_at(t, timeout_s), "mw_watchdog_check_at")
+
+
+def mw_worker_state(worker_id):
+    return _ck(lib().mw_worker_state(worker_id), "mw_worker_state")
+
+
+def mw_heartbeat_epoch(worker_id):
+    return _ck(lib().mw_heartbeat_epoch(worker_id), "mw_heartbeat_epoch")
+
+
 def mw_profile_enable(on):
     return _ck(lib().mw_profile_enable(1 if on else 0), "mw_profile_enable")
 
@@ -286,7 +325,7 @@ def mw_profile_read(kind):
 
 def mw_debug_ring_read(world_id):
     """Bytes of a world's ring header and slots as they are in HBM."""
-    cap = 256 + 64 * 256
+    cap = 256 + 256 * 256
     buf = (C.c_ubyte * cap)()
     n = lib().mw_debug_ring_read(world_id, buf, cap)
     _ck(n, "mw_debug_ring_read")

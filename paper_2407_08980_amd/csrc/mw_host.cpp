@@ -14,10 +14,14 @@
 #include "../../include/mw.h"
 #include "mw_internal.hpp"
 
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
 #include <cstring>
 #include <deque>
 #include <memory>
 #include <mutex>
+#include <thread>
 #include <unordered_map>
 #include <vector>
 
@@ -55,7 +59,8 @@ struct World {
   uint32_t ring_index = kNone;
   uint32_t first_slot = 0;
   uint32_t depth = 0;
-  uint64_t free_mask = 0;  // bit i set: ring slot i is free
+  uint64_t free_mask[kMaxRingDepth / 64] = {};  // bit i set: ring slot i is free
+  uint32_t n_free = 0;
   uint32_t queued = 0;     // operations with all sides posted, not launched yet
   std::vector<uint32_t> inflight;  // op records launched and not yet seen complete
   std::unordered_map<uint32_t, PairQ> pairs;  // key = src * MW_MAX_RANKS + dst
@@ -88,7 +93,7 @@ struct Context {
   int n_workers = 0;
   DeviceConfig cfg{};
   uint32_t max_rings = 1024;
-  uint32_t ring_depth = kMaxRingDepth;
+  uint32_t ring_depth = kDefaultRingDepth;
   bool frozen = false;  // geometry fixed once the first world exists
 
   std::vector<std::unique_ptr<World>> worlds;
@@ -104,6 +109,13 @@ struct Context {
   std::vector<HandleEnt> handles;
   uint32_t handle_cursor = 0;
 
+  // watchdog (Sec. 3.3): per-worker heartbeat epochs and times
+  std::vector<uint64_t> beat_epoch;  // heartbeats received from each worker
+  std::vector<double> last_beat;     // time of the latest one (seconds, caller's or the steady clock)
+  std::vector<uint8_t> beating;      // worker has sent at least one heartbeat: it is being watched
+  std::vector<uint8_t> failed;       // the watchdog has declared the worker failed
+  double wd_timeout = 0;
+
   std::vector<LaunchOp> launch_buf;
   std::vector<void*> stream_buf;
   std::vector<uint32_t> launched_buf;
@@ -111,7 +123,13 @@ struct Context {
 
 std::mutex g_lock;
 std::unique_ptr<Context> g_ctx;
-long g_cfg_chunk = 0, g_cfg_depth = kMaxRingDepth, g_cfg_lds = 0, g_cfg_rings = 1024, g_cfg_handles = 1 << 20;
+// watchdog thread: wakes every period, takes g_lock, inspects the heartbeat table
+std::thread g_wd_thread;
+std::mutex g_wd_mu;
+std::condition_variable g_wd_cv;
+bool g_wd_stop = false;
+bool g_wd_running = false;
+long g_cfg_chunk = 0, g_cfg_depth = kDefaultRingDepth, g_cfg_lds = 0, g_cfg_rings = 1024, g_cfg_handles = 1 << 20;
 
 inline mw_handle make_handle(uint32_t slot, uint32_t gen) { return ((uint64_t)gen << 32) | slot; }
 
@@ -140,6 +158,23 @@ inline void finish_handle(Context& c, uint32_t hslot, int status) {
 }
 
 // ---- ring slots --------------------------------------------------------------------------------
+inline void slot_release(World& w, uint32_t bit) {
+  w.free_mask[bit >> 6] |= 1ull << (bit & 63);
+  w.n_free += 1;
+}
+
+inline uint32_t slot_take(World& w) {  // caller checked n_free > 0
+  for (uint32_t k = 0; k < kMaxRingDepth / 64; ++k) {
+    if (w.free_mask[k]) {
+      uint32_t b = (uint32_t)__builtin_ctzll(w.free_mask[k]);
+      w.free_mask[k] &= ~(1ull << b);
+      w.n_free -= 1;
+      return k * 64 + b;
+    }
+  }
+  return 0;
+}
+
 void release_ring_if_idle(Context& c, World& w) {
   if (w.state == MW_BROKEN && !w.ring_released && w.queued == 0 && w.inflight.empty()) {
     c.free_rings.push_back(w.ring_index);
@@ -151,7 +186,7 @@ void complete_op(Context& c, uint32_t opi) {
   OpRec& op = c.ops[opi];
   World& w = *c.worlds[op.world];
   for (int i = 0; i < op.n_handles; ++i) finish_handle(c, op.handles[i], MW_DONE);
-  w.free_mask |= 1ull << (op.l.slot - w.first_slot);
+  slot_release(w, op.l.slot - w.first_slot);
   op.state = kOpFree;
   c.free_ops.push_back(opi);
 }
@@ -198,13 +233,12 @@ int flush_locked(Context& c) {
     c.ready.pop_front();
     OpRec& op = c.ops[opi];
     World& w = *c.worlds[op.world];
-    if (w.free_mask == 0) retire_world(c, w);
-    if (w.free_mask == 0) {  // ring full: stays queued until earlier operations retire
+    if (w.n_free == 0) retire_world(c, w);
+    if (w.n_free == 0) {  // ring full: stays queued until earlier operations retire
       deferred.push_back(opi);
       continue;
     }
-    uint32_t bit = (uint32_t)__builtin_ctzll(w.free_mask);
-    w.free_mask &= ~(1ull << bit);
+    uint32_t bit = slot_take(w);
     uint32_t slot = w.first_slot + bit;
     uint32_t gen = c.slot_gen[slot] + 1;
     if (gen == 0) gen = 1;
@@ -230,7 +264,7 @@ int flush_locked(Context& c) {
     for (size_t i = c.launched_buf.size(); i-- > 0;) {
       OpRec& op = c.ops[c.launched_buf[i]];
       World& w = *c.worlds[op.world];
-      w.free_mask |= 1ull << (op.l.slot - w.first_slot);
+      slot_release(w, op.l.slot - w.first_slot);
       c.ready.push_front(c.launched_buf[i]);
     }
     return rc;
@@ -466,6 +500,36 @@ int abort_world_locked(Context& c, World& w) {
   return rc != MW_OK ? rc : rc2;
 }
 
+double steady_now() {
+  return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+// One inspection of the heartbeat table at time `now`: every watched worker whose latest heartbeat is
+// older than the timeout is declared failed and the worlds containing it are aborted.
+int watchdog_check_locked(Context& c, double now, double timeout) {
+  int newly = 0;
+  for (size_t k = 0; k < c.beating.size(); ++k) {
+    if (!c.beating[k] || c.failed[k] || !(now - c.last_beat[k] > timeout)) continue;
+    c.failed[k] = 1;
+    ++newly;
+    for (uint32_t wi : c.worlds_of_worker[k]) abort_world_locked(c, *c.worlds[wi]);
+  }
+  return newly;
+}
+
+void stop_watchdog_thread() {  // called WITHOUT g_lock held
+  std::thread t;
+  {
+    std::lock_guard<std::mutex> g(g_wd_mu);
+    if (!g_wd_running) return;
+    g_wd_stop = true;
+    g_wd_cv.notify_all();
+    t = std::move(g_wd_thread);
+    g_wd_running = false;
+  }
+  if (t.joinable()) t.join();
+}
+
 int poll_locked(Context& c, mw_handle h) {
   uint32_t slot = (uint32_t)(h & 0xFFFFFFFFu), gen = (uint32_t)(h >> 32);
   if (slot >= c.handles.size() || gen == 0) return MW_EBADHANDLE;
@@ -508,6 +572,10 @@ int mw_init(int hip_device, int n_workers) {
   int rc = c->dev->init(hip_device, c->cfg);
   if (rc != MW_OK) return rc;
   c->worlds_of_worker.resize((size_t)n_workers);
+  c->beat_epoch.assign((size_t)n_workers, 0);
+  c->last_beat.assign((size_t)n_workers, 0.0);
+  c->beating.assign((size_t)n_workers, 0);
+  c->failed.assign((size_t)n_workers, 0);
   c->slot_gen.assign(c->cfg.total_slots, 0);
   for (uint32_t r = c->max_rings; r-- > 0;) c->free_rings.push_back(r);
   c->handles.resize((size_t)g_cfg_handles);
@@ -516,6 +584,7 @@ int mw_init(int hip_device, int n_workers) {
 }
 
 int mw_shutdown(void) {
+  stop_watchdog_thread();
   std::lock_guard<std::mutex> g(g_lock);
   if (!g_ctx) return MW_ENOTINIT;
   flush_locked(*g_ctx);
@@ -535,6 +604,8 @@ int mw_world_create(int world_id, const int* worker_ids, int n_ranks) {
     for (int j = 0; j < i; ++j)
       if (worker_ids[j] == worker_ids[i]) return MW_EINVAL;
   }
+  for (int i = 0; i < n_ranks; ++i)
+    if (c.failed[(size_t)worker_ids[i]]) return MW_EBROKEN;  // a failed worker is replaced by a NEW worker
   if (c.world_of_id.count(world_id)) return MW_EEXIST;
   if (c.free_rings.empty()) {  // rings of broken worlds come back once their operations retired
     for (auto& wp : c.worlds)
@@ -548,7 +619,7 @@ int mw_world_create(int world_id, const int* worker_ids, int n_ranks) {
   c.free_rings.pop_back();
   w->depth = c.ring_depth;
   w->first_slot = w->ring_index * c.ring_depth;
-  w->free_mask = w->depth == 64 ? ~0ull : ((1ull << w->depth) - 1);
+  for (uint32_t b = 0; b < w->depth; ++b) slot_release(*w, b);
   w->coll_next.assign((size_t)n_ranks, 0);
   RingHeader h{};
   h.world_id = (uint32_t)world_id;
@@ -589,6 +660,72 @@ int mw_worker_abort(int worker_id) {
     if (r != MW_OK) rc = r;
   }
   return rc;
+}
+
+int mw_heartbeat_at(int worker_id, double t) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  Context& c = *g_ctx;
+  if (worker_id < 0 || worker_id >= c.n_workers || !(t == t)) return MW_EINVAL;
+  if (c.failed[(size_t)worker_id]) return MW_EBROKEN;
+  if (!c.beating[(size_t)worker_id] || t > c.last_beat[(size_t)worker_id]) c.last_beat[(size_t)worker_id] = t;
+  c.beating[(size_t)worker_id] = 1;
+  c.beat_epoch[(size_t)worker_id] += 1;
+  return MW_OK;
+}
+
+int mw_heartbeat(int worker_id) { return mw_heartbeat_at(worker_id, steady_now()); }
+
+int mw_watchdog_check_at(double t, double timeout_s) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  if (!(timeout_s >= 0) || !(t == t)) return MW_EINVAL;
+  return watchdog_check_locked(*g_ctx, t, timeout_s);
+}
+
+int mw_watchdog_start(double timeout_s, double period_s) {
+  if (!(timeout_s > 0) || !(period_s > 0)) return MW_EINVAL;
+  {
+    std::lock_guard<std::mutex> g(g_lock);
+    if (!g_ctx) return MW_ENOTINIT;
+    g_ctx->wd_timeout = timeout_s;
+  }
+  std::lock_guard<std::mutex> g(g_wd_mu);
+  if (g_wd_running) return MW_EINVAL;
+  g_wd_stop = false;
+  g_wd_running = true;
+  g_wd_thread = std::thread([timeout_s, period_s] {
+    std::unique_lock<std::mutex> lk(g_wd_mu);
+    while (!g_wd_stop) {
+      lk.unlock();
+      {
+        std::lock_guard<std::mutex> g2(g_lock);
+        if (g_ctx) watchdog_check_locked(*g_ctx, steady_now(), timeout_s);
+      }
+      lk.lock();
+      g_wd_cv.wait_for(lk, std::chrono::duration<double>(period_s), [] { return g_wd_stop; });
+    }
+  });
+  return MW_OK;
+}
+
+int mw_watchdog_stop(void) {
+  stop_watchdog_thread();
+  return MW_OK;
+}
+
+int mw_worker_state(int worker_id) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  if (worker_id < 0 || worker_id >= g_ctx->n_workers) return MW_EINVAL;
+  return g_ctx->failed[(size_t)worker_id] ? MW_BROKEN : MW_ALIVE;
+}
+
+long mw_heartbeat_epoch(int worker_id) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  if (worker_id < 0 || worker_id >= g_ctx->n_workers) return MW_EINVAL;
+  return (long)g_ctx->beat_epoch[(size_t)worker_id];
 }
 
 int mw_world_state(int world_id) {

@@ -14,7 +14,8 @@ namespace mw {
 constexpr int kMaxBufs = 8;          // buffers named by one descriptor (== MW_MAX_COLL_RANKS)
 constexpr int kSlotBytes = 256;      // one ring slot in HBM
 constexpr int kHeaderBytes = 256;    // one ring header in HBM
-constexpr int kMaxRingDepth = 64;
+constexpr int kMaxRingDepth = 256;   // slots per world ring, at most
+constexpr int kDefaultRingDepth = 128;
 
 constexpr int kMaxOpBufs = 16;       // buffers one operation may name (all-gather: 8 sources + 8 destinations)
 

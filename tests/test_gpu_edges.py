@@ -317,7 +317,7 @@ def test_ring_journal_header_and_isolation_across_abort(torch, mw):
     assert wait(mw, hs) == [mw.MW_DONE] * 7
     raw = mw.mw_debug_ring_read(40)
     wid, state, epoch, depth, first_slot, n_ranks = struct.unpack_from("<6I", raw, 0)
-    assert (wid, state, epoch, depth, n_ranks) == (40, 0, 0, 64, 2)
+    assert (wid, state, epoch, depth, n_ranks) == (40, 0, 0, 128, 2)
     used = [s for s in (_slot_fields(raw, i) for i in range(depth)) if s["gen"]]
     assert len(used) == 1
     s = used[0]
@@ -326,7 +326,7 @@ def test_ring_journal_header_and_isolation_across_abort(torch, mw):
     assert s["nchunks"] * s["chunk"] >= n > (s["nchunks"] - 1) * s["chunk"]
     assert s["arrived"] == 0 and s["done_gen"] == s["gen"]  # counter re-armed, completion published
     r42 = mw.mw_debug_ring_read(42)
-    s42 = [x for x in (_slot_fields(r42, i) for i in range(64)) if x["gen"]][0]
+    s42 = [x for x in (_slot_fields(r42, i) for i in range(128)) if x["gen"]][0]
     assert (s42["kind"], s42["nbuf"], s42["nbytes"], s42["world"]) == (2, 3, 4000, 42)
     # abort world 40 while one of its operations waits for a peer: nothing else changes
     before = mw.mw_debug_arena_hash(40)
@@ -347,3 +347,37 @@ def test_ring_journal_header_and_isolation_across_abort(torch, mw):
     with pytest.raises(mw.MwError) as e:
         mw.mw_send(40, 1, 0, bufs[40][0].data_ptr(), n // 2, mw.MW_BF16)
     assert e.value.code == mw.MW_EBROKEN
+
+
+def test_watchdog_cleans_up_a_silent_worker_while_others_stream(torch, mw):
+    """Silent failure on the GPU path: worker 2 stops reporting; the watchdog thread breaks its world only,
+    the transfer it had already been matched for is delivered, the other world keeps moving data."""
+    mw.mw_world_create(1, [0, 1])
+    mw.mw_world_create(2, [0, 2])
+    n = 8 << 20
+    src = {w: torch.full((n,), w, dtype=torch.uint8, device="cuda") for w in (1, 2)}
+    dst = {w: torch.zeros(n, dtype=torch.uint8, device="cuda") for w in (1, 2)}
+    mw.mw_watchdog_start(0.3, 0.02)
+    try:
+        for k in (0, 1, 2):
+            mw.mw_heartbeat(k)
+        last2 = [mw.mw_send(2, 1, 0, src[2].data_ptr(), n // 4, mw.MW_F32), mw.mw_recv(2, 1, 0, dst[2].data_ptr(), n // 4, mw.MW_F32)]
+        lonely = mw.mw_recv(2, 1, 0, dst[2].data_ptr(), n // 4, mw.MW_F32)  # waits for a tensor that never comes
+        moved = 0
+        t0 = time.time()
+        while mw.mw_world_state(2) == mw.MW_ALIVE:
+            assert time.time() - t0 < 10
+            mw.mw_heartbeat(0)
+            mw.mw_heartbeat(1)
+            dst[1].zero_()
+            hs = [mw.mw_send(1, 1, 0, src[1].data_ptr(), n // 4, mw.MW_F32), mw.mw_recv(1, 1, 0, dst[1].data_ptr(), n // 4, mw.MW_F32)]
+            assert wait(mw, hs) == [mw.MW_DONE] * 2 and bool((dst[1] == 1).all())
+            moved += 1
+        assert 0.25 < time.time() - t0 < 3.0 and moved > 3
+        assert wait(mw, last2) == [mw.MW_DONE] * 2 and bool((dst[2] == 2).all())  # matched before the failure: delivered
+        assert mw.mw_poll(lonely) == mw.MW_BROKEN
+        assert mw.mw_world_state(1) == mw.MW_ALIVE and mw.mw_worker_state(2) == mw.MW_BROKEN
+        hs = [mw.mw_send(1, 1, 0, src[1].data_ptr(), n // 4, mw.MW_F32), mw.mw_recv(1, 1, 0, dst[1].data_ptr(), n // 4, mw.MW_F32)]
+        assert wait(mw, hs) == [mw.MW_DONE] * 2
+    finally:
+        mw.mw_watchdog_stop()

@@ -86,7 +86,7 @@ def test_rendezvous_matching_and_batched_launch(ctx):
     a, b = log_entry(ctx, 0), log_entry(ctx, 1)
     assert (a["buf"][:2], a["nbytes"], a["kind"], a["world"]) == ([0x1000, 0x2000], 400, 0, 5)
     assert (b["buf"][:2], b["nbytes"], b["kind"], b["world"]) == ([0x3000, 0x4000], 14, 0, 6)
-    assert a["slot"] // 64 != b["slot"] // 64  # each world has its own ring
+    assert a["slot"] // 128 != b["slot"] // 128  # each world has its own ring
     assert [mw.mw_poll(h) for h in (hs, hr, h2s, h2r)] == [mw.MW_PENDING] * 4
     ctx.mwt_complete(1, 0)
     assert [mw.mw_poll(h) for h in (hs, hr, h2s, h2r)] == [mw.MW_DONE, mw.MW_DONE, mw.MW_PENDING, mw.MW_PENDING]
@@ -244,7 +244,7 @@ def test_ring_slots_recycle_and_full_ring_defers(hostlib):
         assert [mw.mw_poll(h) for h in hs] == [mw.MW_DONE] * 6 and mw.mw_poll(ho) == mw.MW_DONE
     finally:
         mw.mw_shutdown()
-        mw.mw_config_set("ring_depth", 64)
+        mw.mw_config_set("ring_depth", 128)
 
 
 def test_ring_of_a_broken_world_is_reused_only_after_its_operations_retired(hostlib):
@@ -256,7 +256,7 @@ def test_ring_of_a_broken_world_is_reused_only_after_its_operations_retired(host
         mw.mw_send(0, 0, 1, 0x10, 1, mw.MW_F32)
         h = mw.mw_recv(0, 0, 1, 0x20, 1, mw.MW_F32)
         mw.mw_flush()
-        ring0 = log_entry(hostlib, 0)["slot"] // 64
+        ring0 = log_entry(hostlib, 0)["slot"] // 128
         mw.mw_world_abort(0)
         with pytest.raises(mw.MwError) as e:
             mw.mw_world_create(2, [4, 5])  # world 0's operation is still in flight: its ring is not free
@@ -268,7 +268,7 @@ def test_ring_of_a_broken_world_is_reused_only_after_its_operations_retired(host
         mw.mw_recv(2, 0, 1, 0x40, 1, mw.MW_F32)
         mw.mw_flush()
         e2 = log_entry(hostlib, 1)
-        assert e2["slot"] // 64 == ring0 and e2["gen"] >= 1 and e2["world"] == 2
+        assert e2["slot"] // 128 == ring0 and e2["gen"] >= 1 and e2["world"] == 2
         with pytest.raises(mw.MwError) as e:
             mw.mw_world_create(0, [0, 1])  # ids are never reused
         assert e.value.code == mw.MW_EEXIST
