@@ -132,3 +132,39 @@ def test_config5_full_size(gpu, host_pools):
     assert rep["exact"] > 5000 and rep["toleranced"] > 300
     assert grun.world_state == orun.world_state
     assert grun.payload_bytes_done == orun.payload_bytes_done
+
+
+def test_headline_workload_in_the_benchmarks_own_loop(gpu, host_pools):
+    """bench.py's launch configuration: its Workload object, its double-buffered posting loop, its streams.
+    Every step's destinations are compared with the sources on the device, and byte windows of them with
+    what the oracle computes from the input recipe (pool offsets are the benchmark's own seeded draw)."""
+    import torch
+
+    import bench
+    from paper_2407_08980_amd import binding as mw
+    from workloads.data import pool_slice
+
+    dev = torch.device("cuda", 0)
+    mw.mw_init(0, 2 * bench.N_WORLDS)
+    try:
+        wl = bench.Workload(torch, mw, bench.SHAPE, dev)
+        for w in range(bench.N_WORLDS):
+            mw.mw_world_create(w, [2 * w, 2 * w + 1])
+        multi = (list(range(bench.N_WORLDS)), [(0, 1)] * bench.N_WORLDS)
+        rng = np.random.default_rng(7)
+        pool = host_pools.get("bf16")
+        for first in (0, 3, 6):
+            wl.run(3, *multi, first_step=first)  # steps first..first+2, two in flight at a time
+            for s in (first + 1, first + 2):  # the two steps whose destinations are still intact
+                for w in range(bench.N_WORLDS):
+                    d, src = wl.dst[w][s % 2], wl.src[w][s % bench.POOL_K]
+                    assert torch.equal(d, src), (w, s)
+                    for lo, n in windows(wl.nbytes, rng, k=2):
+                        want = oracle.copy_result(pool_slice(pool, "bf16", wl.offsets[w][s % bench.POOL_K] + lo // 2, n))
+                        assert np.array_equal(d[lo:lo + n].cpu().numpy(), want), (w, s, lo)
+            for w in range(bench.N_WORLDS):
+                for d in wl.dst[w]:
+                    d.fill_(0xA5)
+            torch.cuda.synchronize()
+    finally:
+        mw.mw_shutdown()

@@ -402,3 +402,44 @@ def test_post_many_mixed_batch(ctx):
     assert ctx.mwt_launch_size(0) == 2
     ctx.mwt_complete(2, 0)
     assert [mw.mw_poll(handles[i]) for i in (0, 1, 3, 4)] == [mw.MW_DONE] * 4
+
+
+def test_per_operation_host_cost_does_not_grow_with_the_number_of_worlds(hostlib):
+    """Per-world state is looked up by key, never swapped in and out (Sec. 3.2 "State management for multiple
+    worlds"): the host cost of post + match + launch + completion + poll per message must stay flat from
+    4 worlds to 1000 worlds."""
+    import time
+
+    def cost(n_worlds, msgs=20000):
+        mw.mw_init(0, 2 * n_worlds)
+        try:
+            for w in range(n_worlds):
+                mw.mw_world_create(w, [2 * w, 2 * w + 1])
+            batch = 50
+            pbs = []
+            for lo in range(0, min(n_worlds * 4, 400), batch):  # messages spread round-robin over the worlds
+                posts = []
+                for k in range(lo, lo + batch):
+                    w = k % n_worlds
+                    posts.append((mw.POST_SEND, w, 0, 1, 0x1000, 8, mw.MW_F32, mw.STREAM_NONE))
+                    posts.append((mw.POST_RECV, w, 0, 1, 0x2000, 8, mw.MW_F32, mw.STREAM_NONE))
+                pbs.append(mw.PostBatch(posts))
+            best = 1e9
+            for rep in range(3):
+                t0 = time.perf_counter()
+                done = 0
+                while done < msgs:
+                    for pb in pbs:
+                        pb.post()
+                        mw.mw_flush()
+                        hostlib.mwt_complete(batch, 0)
+                        ps = mw.PollSet(list(pb.handles))
+                        assert ps.poll() == 0
+                        done += batch
+                best = min(best, (time.perf_counter() - t0) / done)
+            return best
+        finally:
+            mw.mw_shutdown()
+
+    few, many = cost(4), cost(1000)
+    assert many < 1.6 * few, f"{few * 1e9:.0f} ns per message with 4 worlds, {many * 1e9:.0f} ns with 1000"
