@@ -546,7 +546,8 @@ class HipDevice : public Device {
     cfg_.reduce_lds = cfg.reduce_lds;
   }
 
-  int launch(const LaunchOp* ops, int n, void* const* streams, int n_streams) override {
+  int launch(const LaunchOp* ops, int n, void* const* streams, int n_streams, uint8_t* launched) override {
+    launched_ = launched;
     if (chk(hipSetDevice(dev_))) return MW_EHIP;
     // Each kernel kind has its own stream so that a copy, a broadcast and an all-reduce launch of one
     // flush overlap.  Order every stream used by this flush after the callers' busy streams.
@@ -579,6 +580,7 @@ class HipDevice : public Device {
         expand(ops[i], (uint32_t)i);
         if (ents_.size() == before) {  // every segment already in place: nothing to move, complete now
           __atomic_store_n(&flags_host_[ops[i].slot], ops[i].gen, __ATOMIC_RELEASE);
+          launched[i] = 1;
           continue;
         }
         if (ents_.size() > cap) {  // launch what was gathered before this operation, keep its entries
@@ -854,6 +856,7 @@ class HipDevice : public Device {
       if (chk(hipEventRecord(e1, data_[kind]))) return MW_EHIP;
       prof_.push_back(ProfRec{kind, e0, e1, total_bytes});
     }
+    for (const Ent& e : ents_) launched_[e.group] = 1;  // group = index of the operation in this launch call
     ents_.clear();
     return MW_OK;
   }
@@ -881,6 +884,7 @@ class HipDevice : public Device {
   std::vector<hipEvent_t> prof_free_;
   ProfAcc acc_[kNumKinds];
   std::vector<Ent> ents_, one_;
+  uint8_t* launched_ = nullptr;  // the current launch() call's per-operation result array
   std::vector<uint32_t> chunks_, op_chunks_;
   CopyArgs copy_args_{};
   CollArgs coll_args_{};

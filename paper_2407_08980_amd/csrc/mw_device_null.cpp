@@ -5,6 +5,7 @@
 // the test decides when the recorded operations complete.
 #include <cstring>
 #include <deque>
+#include <mutex>
 #include <vector>
 
 #include "../../include/mw.h"
@@ -27,6 +28,7 @@ struct NullState {
   std::vector<int> launch_streams;    // distinct streams waited on per launch
   int marks = 0;
   bool fail_next_launch = false;
+  std::mutex mu;  // the test hooks may run on another thread than the library calls
 };
 NullState* g_null = nullptr;
 
@@ -40,7 +42,8 @@ class NullDevice : public Device {
   }
   void shutdown() override { g_null = nullptr; }
   void set_config(const DeviceConfig&) override {}
-  int launch(const LaunchOp* ops, int n, void* const*, int n_streams) override {
+  int launch(const LaunchOp* ops, int n, void* const*, int n_streams, uint8_t* launched) override {
+    std::lock_guard<std::mutex> g(st_.mu);
     if (st_.fail_next_launch) {
       st_.fail_next_launch = false;
       return MW_EHIP;
@@ -51,16 +54,19 @@ class NullDevice : public Device {
     for (int i = 0; i < n; ++i) {
       st_.pending.push_back(Recorded{ops[i], id});
       st_.log.push_back(Recorded{ops[i], id});
+      launched[i] = 1;
     }
     return MW_OK;
   }
   int mark_world(uint32_t ring_index, const RingHeader& h) override {
+    std::lock_guard<std::mutex> g(st_.mu);
     st_.headers[ring_index] = h;
     st_.marks += 1;
     return MW_OK;
   }
-  uint32_t flag(uint32_t slot) override { return st_.flags[slot]; }
+  uint32_t flag(uint32_t slot) override { return __atomic_load_n(&st_.flags[slot], __ATOMIC_ACQUIRE); }
   int read_ring(uint32_t ring_index, uint32_t, uint32_t depth, void* out) override {
+    std::lock_guard<std::mutex> g(st_.mu);
     std::memcpy(out, &st_.headers[ring_index], sizeof(RingHeader));
     std::memset(reinterpret_cast<char*>(out) + sizeof(RingHeader), 0, (size_t)depth * kSlotBytes);
     return MW_OK;
@@ -90,10 +96,18 @@ using namespace mw;
 // Hooks for the host-logic tests.
 extern "C" {
 
-int mwt_launch_count(void) { return g_null ? (int)g_null->launch_sizes.size() : -1; }
+int mwt_launch_count(void) {
+  if (!g_null) return -1;
+  std::lock_guard<std::mutex> g(g_null->mu);
+  return (int)g_null->launch_sizes.size();
+}
 int mwt_launch_size(int id) { return g_null && id >= 0 && id < (int)g_null->launch_sizes.size() ? g_null->launch_sizes[id] : -1; }
 int mwt_launch_streams(int id) { return g_null && id >= 0 && id < (int)g_null->launch_streams.size() ? g_null->launch_streams[id] : -1; }
-int mwt_pending(void) { return g_null ? (int)g_null->pending.size() : -1; }
+int mwt_pending(void) {
+  if (!g_null) return -1;
+  std::lock_guard<std::mutex> g(g_null->mu);
+  return (int)g_null->pending.size();
+}
 int mwt_marks(void) { return g_null ? g_null->marks : -1; }
 int mwt_log_size(void) { return g_null ? (int)g_null->log.size() : -1; }
 
@@ -121,11 +135,12 @@ int mwt_log_entry(int i, uint64_t* out) {
 // Let the oldest n launched operations complete (newest first if from_back != 0).
 int mwt_complete(int n, int from_back) {
   if (!g_null) return -1;
+  std::lock_guard<std::mutex> g(g_null->mu);
   int done = 0;
   while (done < n && !g_null->pending.empty()) {
     Recorded r = from_back ? g_null->pending.back() : g_null->pending.front();
     if (from_back) g_null->pending.pop_back(); else g_null->pending.pop_front();
-    g_null->flags[r.op.slot] = r.op.gen;
+    __atomic_store_n(&g_null->flags[r.op.slot], r.op.gen, __ATOMIC_RELEASE);
     ++done;
   }
   return done;

@@ -16,7 +16,6 @@
 
 #include <atomic>
 #include <chrono>
-#include <condition_variable>
 #include <cstring>
 #include <deque>
 #include <memory>
@@ -94,7 +93,6 @@ struct Context {
   DeviceConfig cfg{};
   uint32_t max_rings = 1024;
   uint32_t ring_depth = kDefaultRingDepth;
-  bool frozen = false;  // geometry fixed once the first world exists
 
   std::vector<std::unique_ptr<World>> worlds;
   std::unordered_map<int, uint32_t> world_of_id;  // the key-value store of per-world state
@@ -114,20 +112,19 @@ struct Context {
   std::vector<double> last_beat;     // time of the latest one (seconds, caller's or the steady clock)
   std::vector<uint8_t> beating;      // worker has sent at least one heartbeat: it is being watched
   std::vector<uint8_t> failed;       // the watchdog has declared the worker failed
-  double wd_timeout = 0;
 
   std::vector<LaunchOp> launch_buf;
   std::vector<void*> stream_buf;
   std::vector<uint32_t> launched_buf;
+  std::vector<uint8_t> launched_flags;
 };
 
 std::mutex g_lock;
 std::unique_ptr<Context> g_ctx;
 // watchdog thread: wakes every period, takes g_lock, inspects the heartbeat table
 std::thread g_wd_thread;
-std::mutex g_wd_mu;
-std::condition_variable g_wd_cv;
-bool g_wd_stop = false;
+std::mutex g_wd_mu;  // guards g_wd_thread / g_wd_running
+std::atomic<bool> g_wd_stop{false};
 bool g_wd_running = false;
 long g_cfg_chunk = 0, g_cfg_depth = kDefaultRingDepth, g_cfg_lds = 0, g_cfg_rings = 1024, g_cfg_handles = 1 << 20;
 
@@ -257,26 +254,24 @@ int flush_locked(Context& c) {
   }
   c.ready.swap(deferred);
   if (c.launch_buf.empty()) return MW_OK;
+  c.launched_flags.assign(c.launch_buf.size(), 0);
   int rc = c.dev->launch(c.launch_buf.data(), (int)c.launch_buf.size(), c.stream_buf.data(),
-                         (int)c.stream_buf.size());
-  if (rc != MW_OK) {
-    // Nothing was enqueued for these operations: put them back, slots freed.
-    for (size_t i = c.launched_buf.size(); i-- > 0;) {
-      OpRec& op = c.ops[c.launched_buf[i]];
-      World& w = *c.worlds[op.world];
-      slot_release(w, op.l.slot - w.first_slot);
-      c.ready.push_front(c.launched_buf[i]);
-    }
-    return rc;
-  }
-  for (uint32_t opi : c.launched_buf) {
+                         (int)c.stream_buf.size(), c.launched_flags.data());
+  // Operations the device took are in flight; on a failure the others go back to the queue, slots freed.
+  for (size_t i = c.launched_buf.size(); i-- > 0;) {
+    uint32_t opi = c.launched_buf[i];
     OpRec& op = c.ops[opi];
     World& w = *c.worlds[op.world];
-    op.state = kOpInflight;
-    w.queued -= 1;
-    w.inflight.push_back(opi);
+    if (c.launched_flags[i]) {
+      op.state = kOpInflight;
+      w.queued -= 1;
+      w.inflight.push_back(opi);
+    } else {
+      slot_release(w, op.l.slot - w.first_slot);
+      c.ready.push_front(opi);
+    }
   }
-  return MW_OK;
+  return rc;
 }
 
 // An operation with all sides present: give it a record and queue it for the next launch.  `l` has
@@ -522,8 +517,7 @@ void stop_watchdog_thread() {  // called WITHOUT g_lock held
   {
     std::lock_guard<std::mutex> g(g_wd_mu);
     if (!g_wd_running) return;
-    g_wd_stop = true;
-    g_wd_cv.notify_all();
+    g_wd_stop.store(true);
     t = std::move(g_wd_thread);
     g_wd_running = false;
   }
@@ -637,7 +631,6 @@ int mw_world_create(int world_id, const int* worker_ids, int n_ranks) {
   for (int i = 0; i < n_ranks; ++i) c.worlds_of_worker[(size_t)worker_ids[i]].push_back(wi);
   c.world_of_id.emplace(world_id, wi);
   c.worlds.push_back(std::move(w));
-  c.frozen = true;
   return MW_OK;
 }
 
@@ -688,22 +681,20 @@ int mw_watchdog_start(double timeout_s, double period_s) {
   {
     std::lock_guard<std::mutex> g(g_lock);
     if (!g_ctx) return MW_ENOTINIT;
-    g_ctx->wd_timeout = timeout_s;
   }
   std::lock_guard<std::mutex> g(g_wd_mu);
   if (g_wd_running) return MW_EINVAL;
-  g_wd_stop = false;
+  g_wd_stop.store(false);
   g_wd_running = true;
   g_wd_thread = std::thread([timeout_s, period_s] {
-    std::unique_lock<std::mutex> lk(g_wd_mu);
-    while (!g_wd_stop) {
-      lk.unlock();
+    while (!g_wd_stop.load()) {
       {
         std::lock_guard<std::mutex> g2(g_lock);
         if (g_ctx) watchdog_check_locked(*g_ctx, steady_now(), timeout_s);
       }
-      lk.lock();
-      g_wd_cv.wait_for(lk, std::chrono::duration<double>(period_s), [] { return g_wd_stop; });
+      // sleep one period in slices so that a stop request is honoured within ~10 ms
+      for (double left = period_s; left > 0 && !g_wd_stop.load(); left -= 0.01)
+        std::this_thread::sleep_for(std::chrono::duration<double>(left < 0.01 ? left : 0.01));
     }
   });
   return MW_OK;

@@ -108,8 +108,10 @@ class Device {
   virtual void shutdown() = 0;
   virtual void set_config(const DeviceConfig& cfg) = 0;
   // Launch `n` operations (any mix of kinds, any worlds), ordered after the work already
-  // enqueued on each of `streams` (hipStream_t as void*, NULL = null stream).  Returns 0 or MW_EHIP.
-  virtual int launch(const LaunchOp* ops, int n, void* const* streams, int n_streams) = 0;
+  // enqueued on each of `streams` (hipStream_t as void*, NULL = null stream).  Returns 0 or MW_EHIP;
+  // launched[i] is set to 1 for every operation that was enqueued on the device (all of them on
+  // success; on failure the others were not and may be retried).
+  virtual int launch(const LaunchOp* ops, int n, void* const* streams, int n_streams, uint8_t* launched) = 0;
   // Write a ring header (world create / abort marker).  Asynchronous, on the library's stream.
   virtual int mark_world(uint32_t ring_index, const RingHeader& h) = 0;
   // Host-visible completion word of a slot (acquire load of the pinned mirror).
