@@ -30,8 +30,8 @@ POOL_K = 4
 # HBM bytes per mw_k_copy launch of this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (summary in
 # profiles/mw_k_copy_config2_hbm_counters.txt).  Valid only for the kernel source it was taken with: once
 # csrc/mw_device.hip changes, `traffic` is reported as null until the counters are taken again.
-PMC_TRAFFIC = {"sha256": "1db661e1838074510a6ba65d9e3d72fa13ca32c48904d7bd85eccf273c26c49a",
-               "bytes_per_launch": 8590999712}
+PMC_TRAFFIC = {"sha256": "08878643f4a51e2b9f905969ec7b0c4c54749988ec44f20cc797a22a36baf2f1",
+               "bytes_per_launch": 8591010623}
 
 
 def parse():
