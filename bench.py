@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--reps", type=int, default=5, help="repetitions of the multi-/single-world comparison")
-    ap.add_argument("--cpu-steps", type=int, default=6, help="steps of the workload the CPU oracle is timed on")
+    ap.add_argument("--cpu-steps", type=int, default=24, help="steps of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", type=int, default=0,
                     help="also run this many plain 1 GiB device copies (torch copy_) before the timed region: the "

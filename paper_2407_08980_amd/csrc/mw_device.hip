@@ -361,21 +361,31 @@ struct Acc<true> {
   }
 };
 
-// Register path: every thread holds U vectors of every rank and folds them in, in rank order.
-template <bool BF16, int NB>
-__device__ __forceinline__ void reduce_vectors(const rsrc_t* w, int nbuf, uint32_t wmask, uint32_t nvec) {
+// Register path, instantiated for the exact number of ranks N so that the loads of all ranks are
+// issued back to back with no branch between them: every thread holds U vectors of every rank and
+// folds them in, in rank order.  ALL: every rank receives the sum; otherwise only `root` does.
+template <bool BF16, int N, bool ALL>
+__device__ __forceinline__ void reduce_vectors(const uint64_t* buf, uint64_t off, uint32_t len, uint32_t root,
+                                               uint32_t nvec) {
   constexpr int U = kReduceU;
   const uint32_t step = kReduceWG * U;
+  rsrc_t w[N];
+#pragma unroll
+  for (int r = 0; r < N; ++r) w[r] = window(buf[r] + off, len);
+  rsrc_t wroot = w[0];
+  if (!ALL) {
+#pragma unroll
+    for (int r = 1; r < N; ++r)
+      if ((uint32_t)r == root) wroot = w[r];
+  }
   for (uint32_t i = threadIdx.x; i < nvec; i += step) {
-    u32x4 x[NB][U];
+    u32x4 x[N][U];
 #pragma unroll
-    for (int r = 0; r < NB; ++r) {
-      if (r < nbuf) {
+    for (int r = 0; r < N; ++r) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          uint32_t j = i + u * kReduceWG;
-          if (j < nvec) x[r][u] = Io<u32x4>::ld(w[r], j * 16);
-        }
+      for (int u = 0; u < U; ++u) {
+        uint32_t j = i + u * kReduceWG;
+        if (j < nvec) x[r][u] = Io<u32x4>::ld(w[r], j * 16);
       }
     }
     u32x4 y[U];
@@ -384,20 +394,46 @@ __device__ __forceinline__ void reduce_vectors(const rsrc_t* w, int nbuf, uint32
       Acc<BF16> acc;
       acc.init(x[0][u]);
 #pragma unroll
-      for (int r = 1; r < NB; ++r)
-        if (r < nbuf) acc.add(x[r][u]);
+      for (int r = 1; r < N; ++r) acc.add(x[r][u]);
       y[u] = acc.out();
     }
+    if (ALL) {
 #pragma unroll
-    for (int r = 0; r < NB; ++r) {
-      if (r < nbuf && ((wmask >> r) & 1u)) {
+      for (int r = 0; r < N; ++r) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           uint32_t j = i + u * kReduceWG;
           if (j < nvec) Io<u32x4>::st(w[r], j * 16, y[u]);
         }
       }
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        uint32_t j = i + u * kReduceWG;
+        if (j < nvec) Io<u32x4>::st(wroot, j * 16, y[u]);
+      }
     }
+  }
+}
+
+template <bool BF16, int N>
+__device__ __forceinline__ void reduce_vectors_n(const uint64_t* buf, uint64_t off, uint32_t len, uint32_t wmask,
+                                                 uint32_t nvec) {
+  if (wmask == (1u << N) - 1) reduce_vectors<BF16, N, true>(buf, off, len, 0, nvec);
+  else reduce_vectors<BF16, N, false>(buf, off, len, (uint32_t)__builtin_ctz(wmask), nvec);
+}
+
+template <bool BF16>
+__device__ __forceinline__ void reduce_vectors_any(const uint64_t* buf, uint64_t off, uint32_t len, int nbuf,
+                                                   uint32_t wmask, uint32_t nvec) {
+  switch (nbuf) {
+    case 2: reduce_vectors_n<BF16, 2>(buf, off, len, wmask, nvec); break;
+    case 3: reduce_vectors_n<BF16, 3>(buf, off, len, wmask, nvec); break;
+    case 4: reduce_vectors_n<BF16, 4>(buf, off, len, wmask, nvec); break;
+    case 5: reduce_vectors_n<BF16, 5>(buf, off, len, wmask, nvec); break;
+    case 6: reduce_vectors_n<BF16, 6>(buf, off, len, wmask, nvec); break;
+    case 7: reduce_vectors_n<BF16, 7>(buf, off, len, wmask, nvec); break;
+    default: reduce_vectors_n<BF16, 8>(buf, off, len, wmask, nvec); break;
   }
 }
 
@@ -512,15 +548,9 @@ __global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs a, RingS
     if (LDS) {
       if (bf16) reduce_vectors_lds<true>(w, (int)nbuf, wmask, nvec, tile);
       else reduce_vectors_lds<false>(w, (int)nbuf, wmask, nvec, tile);
-    } else if (nbuf <= 2) {
-      if (bf16) reduce_vectors<true, 2>(w, (int)nbuf, wmask, nvec);
-      else reduce_vectors<false, 2>(w, (int)nbuf, wmask, nvec);
-    } else if (nbuf <= 4) {
-      if (bf16) reduce_vectors<true, 4>(w, (int)nbuf, wmask, nvec);
-      else reduce_vectors<false, 4>(w, (int)nbuf, wmask, nvec);
     } else {
-      if (bf16) reduce_vectors<true, kMaxBufs>(w, (int)nbuf, wmask, nvec);
-      else reduce_vectors<false, kMaxBufs>(w, (int)nbuf, wmask, nvec);
+      if (bf16) reduce_vectors_any<true>(buf, off, (uint32_t)len, (int)nbuf, wmask, nvec);
+      else reduce_vectors_any<false>(buf, off, (uint32_t)len, (int)nbuf, wmask, nvec);
     }
   }
   const uint32_t first = nvec * (16 / isz);
