@@ -552,12 +552,14 @@ def run_config1(torch, mw, dev, reps):
 
 def run_config5(torch, mw, dev, n_ops, reps):
     """Mixed scale-out: the seeded 10 000-operation trace (64 worlds of 2-4 over 32 workers, 70/20/10 %
-    p2p / broadcast / all-reduce, 4 KiB - 64 MiB, fp32/bf16, three worker aborts), <= 64 outstanding.
+    p2p / broadcast / all-reduce, 4 KiB - 64 MiB, fp32/bf16, three worker aborts), <= 64 outstanding (two
+    half-windows of 32 in flight).
     Buffers are slices of one pre-filled slab so that no initialisation runs inside the timed region."""
     import workloads
 
-    t = workloads.config5(n_ops=n_ops)
+    t = workloads.config5(n_ops=n_ops, window=32)  # two half-windows of 32 in flight: <= 64 outstanding
     slab_bytes = 40 << 30
+    half = slab_bytes // 2
     slab = torch.empty(slab_bytes, dtype=torch.uint8, device=dev)
     g = torch.Generator(device=dev)
     g.manual_seed(5)
@@ -569,13 +571,13 @@ def run_config5(torch, mw, dev, n_ops, reps):
     kind_of = {"send": mw.POST_SEND, "recv": mw.POST_RECV, "bcast": mw.POST_BROADCAST, "allreduce": mw.POST_ALLREDUCE_SUM}
 
     def segments(world_base):
-        segs, posts, off, where = [], [], 0, {}
+        segs, posts, off, where, seg = [], [], 0, {}, 0
         for op in t.ops:
             if op.kind in kind_of:
                 if op.buf not in where:
                     nb = (t.bufs[op.buf].nbytes + 255) & ~255
-                    assert off + nb <= slab_bytes, "slab too small for a window"
-                    where[op.buf] = off
+                    assert off + nb <= half, "slab too small for a half-window"
+                    where[op.buf] = (seg % 2) * half + off  # consecutive half-windows use different halves
                     off += nb
                 posts.append((kind_of[op.kind], world_base + op.world, op.a, max(op.b, 0), base + where[op.buf], op.count,
                               mw.DTYPES[op.dtype], mw.STREAM_NONE))
@@ -589,8 +591,14 @@ def run_config5(torch, mw, dev, n_ops, reps):
                     segs.append(("post", mw.PostBatch(posts)))
                     posts = []
                 segs.append(("wait", None))
-                off, where = 0, {}
+                off, where, seg = 0, {}, seg + 1
         return segs
+
+    def drain(sets):
+        for ps in sets:
+            if ps.n:
+                while ps.poll():
+                    pass
 
     def run(world_base):
         for op in t.ops:
@@ -599,21 +607,19 @@ def run_config5(torch, mw, dev, n_ops, reps):
         segs = segments(world_base)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        live = []
+        live, prev = [], []
         for kind, x in segs:
             if kind == "post":
                 x.post(check=False)
                 live.append(x)
             elif kind == "abort":
                 mw.mw_worker_abort(x)
-            else:
+            else:  # end of a half-window: launch it, then wait for the one before it
                 mw.mw_flush()
-                sets = [mw.PollSet([h for h in pb.handles if h]) for pb in live]
-                while mw.mw_pending_ops():
-                    for ps in sets:
-                        if ps.n:
-                            ps.poll()
-                live = []
+                cur = [mw.PollSet([h for h in pb.handles if h]) for pb in live]
+                drain(prev)
+                prev, live = cur, []
+        drain(prev)
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
