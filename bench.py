@@ -30,8 +30,8 @@ POOL_K = 4
 # HBM bytes per mw_k_copy launch of this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (summary in
 # profiles/mw_k_copy_config2_hbm_counters.txt).  Valid only for the kernel source it was taken with: once
 # csrc/mw_device.hip changes, `traffic` is reported as null until the counters are taken again.
-PMC_TRAFFIC = {"sha256": "08878643f4a51e2b9f905969ec7b0c4c54749988ec44f20cc797a22a36baf2f1",
-               "bytes_per_launch": 8591010623}
+PMC_TRAFFIC = {"sha256": "00f32cea735e3154a4e5ad96af8ecb98b25b4ba2f77572638211a21b8988935f",
+               "bytes_per_launch": 8590989131}
 
 
 def parse():
