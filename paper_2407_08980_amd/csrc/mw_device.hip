@@ -577,31 +577,9 @@ inline uint32_t floor_log2(uint64_t v) { return 63u - (uint32_t)__builtin_clzll(
 class HipDevice : public Device {
  public:
   int init(int hip_device, const DeviceConfig& cfg) override {
-    cfg_ = cfg;
-    dev_ = hip_device;
-    int count = 0;
-    if (chk(hipGetDeviceCount(&count)) || hip_device < 0 || hip_device >= count) return MW_EHIP;
-    if (chk(hipSetDevice(dev_))) return MW_EHIP;
-    const size_t hdr_bytes = (size_t)cfg.total_rings * sizeof(RingHeader);
-    const size_t slot_bytes = (size_t)cfg.total_slots * sizeof(RingSlot);
-    if (chk(hipMalloc(&arena_, hdr_bytes + slot_bytes))) return MW_EHIP;
-    if (chk(hipMemset(arena_, 0, hdr_bytes + slot_bytes))) return MW_EHIP;
-    headers_ = reinterpret_cast<RingHeader*>(arena_);
-    slots_ = reinterpret_cast<RingSlot*>(reinterpret_cast<char*>(arena_) + hdr_bytes);
-    if (chk(hipHostMalloc(&flags_host_, (size_t)cfg.total_slots * sizeof(uint32_t), hipHostMallocMapped | hipHostMallocCoherent)))
-      return MW_EHIP;
-    std::memset(flags_host_, 0, (size_t)cfg.total_slots * sizeof(uint32_t));
-    if (chk(hipHostGetDevicePointer(reinterpret_cast<void**>(&flags_dev_), flags_host_, 0))) return MW_EHIP;
-    for (auto& kind : lanes_)
-      for (auto& st : kind)
-        if (chk(hipStreamCreateWithFlags(&st, hipStreamNonBlocking))) return MW_EHIP;
-    if (chk(hipStreamCreateWithFlags(&ctl_, hipStreamNonBlocking))) return MW_EHIP;
-    dep_events_.resize(kDepEvents);
-    for (auto& e : dep_events_)
-      if (chk(hipEventCreateWithFlags(&e, hipEventDisableTiming))) return MW_EHIP;
-    if (chk(hipDeviceSynchronize())) return MW_EHIP;
-    ready_ = true;
-    return MW_OK;
+    int rc = init_impl(hip_device, cfg);
+    if (rc != MW_OK) release();  // nothing half-built survives a failed init
+    return rc;
   }
 
   void shutdown() override {
@@ -610,18 +588,7 @@ class HipDevice : public Device {
     for (auto& kind : lanes_)
       for (auto& st : kind) (void)hipStreamSynchronize(st);
     (void)hipStreamSynchronize(ctl_);
-    for (auto& e : dep_events_) (void)hipEventDestroy(e);
-    for (auto& r : prof_) {
-      (void)hipEventDestroy(r.start);
-      (void)hipEventDestroy(r.stop);
-    }
-    for (auto& e : prof_free_) (void)hipEventDestroy(e);
-    for (auto& kind : lanes_)
-      for (auto& st : kind) (void)hipStreamDestroy(st);
-    (void)hipStreamDestroy(ctl_);
-    (void)hipFree(arena_);
-    (void)hipHostFree(flags_host_);
-    ready_ = false;
+    release();
   }
 
   void set_config(const DeviceConfig& cfg) override {
@@ -763,6 +730,61 @@ class HipDevice : public Device {
     double ms = 0;
     uint64_t bytes = 0;
   };
+
+  int init_impl(int hip_device, const DeviceConfig& cfg) {
+    cfg_ = cfg;
+    dev_ = hip_device;
+    int count = 0;
+    if (chk(hipGetDeviceCount(&count)) || hip_device < 0 || hip_device >= count) return MW_EHIP;
+    if (chk(hipSetDevice(dev_))) return MW_EHIP;
+    const size_t hdr_bytes = (size_t)cfg.total_rings * sizeof(RingHeader);
+    const size_t slot_bytes = (size_t)cfg.total_slots * sizeof(RingSlot);
+    if (chk(hipMalloc(&arena_, hdr_bytes + slot_bytes))) return MW_EHIP;
+    if (chk(hipMemset(arena_, 0, hdr_bytes + slot_bytes))) return MW_EHIP;
+    headers_ = reinterpret_cast<RingHeader*>(arena_);
+    slots_ = reinterpret_cast<RingSlot*>(reinterpret_cast<char*>(arena_) + hdr_bytes);
+    if (chk(hipHostMalloc(&flags_host_, (size_t)cfg.total_slots * sizeof(uint32_t),
+                          hipHostMallocMapped | hipHostMallocCoherent)))
+      return MW_EHIP;
+    std::memset(flags_host_, 0, (size_t)cfg.total_slots * sizeof(uint32_t));
+    if (chk(hipHostGetDevicePointer(reinterpret_cast<void**>(&flags_dev_), flags_host_, 0))) return MW_EHIP;
+    for (auto& kind : lanes_)
+      for (auto& st : kind)
+        if (chk(hipStreamCreateWithFlags(&st, hipStreamNonBlocking))) return MW_EHIP;
+    if (chk(hipStreamCreateWithFlags(&ctl_, hipStreamNonBlocking))) return MW_EHIP;
+    dep_events_.assign(kDepEvents, nullptr);
+    for (auto& e : dep_events_)
+      if (chk(hipEventCreateWithFlags(&e, hipEventDisableTiming))) return MW_EHIP;
+    if (chk(hipDeviceSynchronize())) return MW_EHIP;
+    ready_ = true;
+    return MW_OK;
+  }
+
+  // Free whatever exists (also after a partial init).
+  void release() {
+    for (auto& e : dep_events_)
+      if (e) (void)hipEventDestroy(e);
+    dep_events_.clear();
+    for (auto& r : prof_) {
+      (void)hipEventDestroy(r.start);
+      (void)hipEventDestroy(r.stop);
+    }
+    prof_.clear();
+    for (auto& e : prof_free_) (void)hipEventDestroy(e);
+    prof_free_.clear();
+    for (auto& kind : lanes_)
+      for (auto& st : kind) {
+        if (st) (void)hipStreamDestroy(st);
+        st = nullptr;
+      }
+    if (ctl_) (void)hipStreamDestroy(ctl_);
+    ctl_ = nullptr;
+    if (arena_) (void)hipFree(arena_);
+    arena_ = nullptr;
+    if (flags_host_) (void)hipHostFree(flags_host_);
+    flags_host_ = nullptr;
+    ready_ = false;
+  }
 
   bool chk(hipError_t e) {
     if (e == hipSuccess) return false;
