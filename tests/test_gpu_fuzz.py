@@ -1,0 +1,181 @@
+"""Random, deliberately messy sequences of all eight operations and aborts, with payload, through the C ABI
+on the GPU and through the oracle: sides that never meet, disagreeing counts / dtypes / roots / kinds, ranks
+running ahead in their collective sequence, world and worker aborts.  One operation completes at a time, so
+the result is unique: after every few steps the state of every handle and every byte of every buffer must
+agree (operations that end mismatched, broken or pending must not have touched memory).  Values are small
+integers and are re-drawn before sums could leave the exactly representable range, so reductions compare
+bit for bit as well."""
+
+import time
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import BF16, BROKEN, DONE, F32, MISMATCH, PENDING, WorldOracle, f32_to_bf16_bits
+from oracle.mw_oracle import OracleError
+
+N_WORKERS = 8
+BUF_BYTES = 4096
+F32_BUFS, BF16_BUFS = 4, 3  # per worker
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    torch.cuda.set_device(0)
+    return torch
+
+
+@pytest.fixture
+def mw(torch):
+    from paper_2407_08980_amd import binding
+
+    binding.lib()
+    binding.mw_init(0, N_WORKERS)
+    yield binding
+    binding.mw_shutdown()
+
+
+def fresh_arena(rng):
+    """Every worker's buffers, filled with -1, 0, +1 in the buffer's own element type."""
+    per = F32_BUFS + BF16_BUFS
+    arena = np.empty((N_WORKERS, per, BUF_BYTES), np.uint8)
+    for k in range(N_WORKERS):
+        for j in range(per):
+            if j < F32_BUFS:
+                v = rng.integers(-1, 2, size=BUF_BYTES // 4).astype(np.float32)
+                arena[k, j] = v.view(np.uint8)
+            else:
+                v = rng.integers(-1, 2, size=BUF_BYTES // 2).astype(np.float32)
+                arena[k, j] = f32_to_bf16_bits(v).view(np.uint8)
+    return arena
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_random_sequences_with_payload_agree_with_the_oracle(torch, mw, seed):
+    STATE = {mw.MW_DONE: DONE, mw.MW_PENDING: PENDING, mw.MW_BROKEN: BROKEN, mw.MW_EMISMATCH: MISMATCH}
+    rng = np.random.default_rng(7000 + seed)
+    per = F32_BUFS + BF16_BUFS
+    host = fresh_arena(rng)  # the oracle's memory
+    dev = torch.from_numpy(host.copy()).cuda()  # the library's memory
+    base = dev.data_ptr()
+
+    def pick(worker, dtype, other=None):
+        lo, hi = (0, F32_BUFS) if dtype == F32 else (F32_BUFS, per)
+        j = int(rng.integers(lo, hi))
+        while other is not None and j == other:
+            j = int(rng.integers(lo, hi))
+        return j
+
+    o = WorldOracle(N_WORKERS)
+    worlds, pairs, reducing = {}, [], {}
+    next_world, reductions_done = 0, 0
+
+    def both(ofn, gfn, is_reduction):
+        try:
+            oh, oerr = ofn(), None
+        except OracleError as e:
+            oh, oerr = None, e.code
+        try:
+            gh, gerr = gfn(), None
+        except mw.MwError as e:
+            gh, gerr = None, e.code
+        if oerr == "EINVAL":
+            assert gerr == mw.MW_EINVAL
+        elif oerr is None and gerr == mw.MW_EBROKEN:
+            assert o.status(oh) == BROKEN
+        else:
+            assert oerr is None and gerr is None, (oerr, gerr)
+            pairs.append((oh, gh))
+            if is_reduction:
+                reducing[oh] = False  # not yet counted as done
+
+    def settle():
+        """Launch what is matched and wait until nothing is queued or in flight."""
+        mw.mw_flush()
+        t0 = time.time()
+        while mw.mw_pending_ops():  # an operation that matched in this step includes the newest handle
+            for _, gh in pairs[-4:]:
+                mw.mw_poll(gh)
+            assert time.time() - t0 < 30, "operations did not complete"
+
+    n_steps = 1200
+    for step in range(n_steps):
+        r = rng.random()
+        if r < 0.04 or not worlds:
+            size = int(rng.integers(1, 4))
+            members = tuple(int(x) for x in rng.choice(N_WORKERS, size=size, replace=False))
+            o.create(next_world, members)
+            mw.mw_world_create(next_world, list(members))
+            worlds[next_world] = members
+            next_world += 1
+        elif r < 0.05:
+            w = int(rng.choice(list(worlds)))
+            o.abort_world(w)
+            mw.mw_world_abort(w)
+        elif r < 0.053:
+            k = int(rng.integers(0, N_WORKERS))
+            o.abort_worker(k)
+            mw.mw_worker_abort(k)
+        else:
+            w = int(rng.choice(list(worlds)))
+            members = worlds[w]
+            n = len(members)
+            a, b = int(rng.integers(0, n)), int(rng.integers(0, n))
+            if rng.random() < 0.02:
+                a = int(rng.choice([-1, n]))
+            count = int(rng.choice([0, 5, 64, 64, 64, 64, 64, 333]))
+            dt, gdt = (F32, mw.MW_F32) if rng.random() < 0.85 else (BF16, mw.MW_BF16)
+            kind = int(rng.integers(0, 8))
+            # the buffers belong to the worker that posts: the sender for a send, the receiver for a receive,
+            # rank a for a collective
+            poster = members[b] if (kind == 1 and 0 <= b < n) else members[a] if 0 <= a < n else members[0]
+            j1 = pick(poster, dt)
+            j2 = pick(poster, dt, j1)
+            h1, h2 = host[poster, j1], host[poster, j2]
+            d1 = base + (poster * per + j1) * BUF_BYTES
+            d2 = base + (poster * per + j2) * BUF_BYTES
+            if kind == 0:
+                both(lambda: o.post_send(w, a, b, h1, count, dt), lambda: mw.mw_send(w, a, b, d1, count, gdt), False)
+            elif kind == 1:
+                both(lambda: o.post_recv(w, a, b, h1, count, dt), lambda: mw.mw_recv(w, a, b, d1, count, gdt), False)
+            elif kind == 2:
+                both(lambda: o.post_broadcast(w, a, b, h1, count, dt), lambda: mw.mw_broadcast(w, a, b, d1, count, gdt), False)
+            elif kind == 3:
+                both(lambda: o.post_allreduce(w, a, h1, count, dt), lambda: mw.mw_allreduce_sum(w, a, d1, count, gdt), True)
+            elif kind == 4:
+                both(lambda: o.post_reduce(w, a, b, h1, count, dt), lambda: mw.mw_reduce_sum(w, a, b, d1, count, gdt), True)
+            elif kind == 5:
+                both(lambda: o.post_all_gather(w, a, h1, h2, count, dt),
+                     lambda: mw.mw_all_gather(w, a, d1, d2, count, gdt), False)
+            elif kind == 6:
+                both(lambda: o.post_gather(w, a, b, h1, h2, count, dt),
+                     lambda: mw.mw_gather(w, a, b, d1, d2, count, gdt), False)
+            else:
+                both(lambda: o.post_scatter(w, a, b, h1, h2, count, dt),
+                     lambda: mw.mw_scatter(w, a, b, d1, d2, count, gdt), False)
+        settle()
+        for oh in reducing:
+            if not reducing[oh] and o.status(oh) == DONE:
+                reducing[oh] = True
+                reductions_done += 1
+        if step % 8 == 0 or step == n_steps - 1:
+            for oh, gh in pairs:
+                assert STATE[mw.mw_poll(gh)] == o.status(oh), (step, oh)
+            got = dev.cpu().numpy()
+            assert np.array_equal(got, host), (step, np.argwhere(got != host)[:4])
+        # A reduction over n ranks multiplies the largest magnitude by at most n and is counted n times here (once
+        # per rank's handle).  The count is at most 8 + 3 when new values are drawn, so magnitudes stay below
+        # 3 * 3 * 3 * 2 = 54, inside what bf16 holds exactly (256).  Nothing is in flight after settle().
+        if reductions_done >= 9:
+            host[:] = fresh_arena(rng)
+            dev.copy_(torch.from_numpy(host))
+            torch.cuda.synchronize()
+            reductions_done = 0
+    seen = {o.status(oh) for oh, _ in pairs}
+    assert {DONE, PENDING, BROKEN, MISMATCH} <= seen, seen
+    assert sum(reducing.values()) >= 20  # the run did complete reductions
