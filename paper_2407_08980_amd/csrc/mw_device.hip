@@ -38,14 +38,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kCopyWG = 1024;   // threads per workgroup, copy / broadcast
 constexpr int kCopyU = 4;       // 16-byte vectors in flight per thread
-#ifndef MW_REDUCE_WG
-#define MW_REDUCE_WG 1024
-#endif
-#ifndef MW_REDUCE_U
-#define MW_REDUCE_U 1
-#endif
-constexpr int kReduceWG = MW_REDUCE_WG;  // threads per workgroup, all-reduce
-constexpr int kReduceU = MW_REDUCE_U;    // 16-byte vectors per rank in flight per thread
+constexpr int kReduceWG = 1024;  // threads per workgroup, all-reduce
+constexpr int kReduceU = 1;      // 16-byte vectors per rank in flight per thread, LDS-staged path
+// Register path: 16-byte vectors per rank in flight per thread, by number of ranks.  Two ranks give a
+// thread only two loads per vector; a second vector brings it to the four that the other counts have.
+constexpr int reduce_u(int n) { return n == 2 ? 2 : 1; }
 constexpr int kCopyMax = 72;    // entries per copy launch (kernel arguments stay under 4 KiB)
 constexpr int kCollMax = 36;    // entries per fan-out / reduce launch
 
@@ -53,7 +50,8 @@ constexpr int kCollMax = 36;    // entries per fan-out / reduce launch
 // scatter n copy entries, a broadcast one fan-out entry, an all-gather n (or more) fan-out entries,
 // an (all-)reduce one reduce entry.  All entries of an operation share its ring slot; `op_chunks`
 // is the chunk count of the whole operation, which is what the arrival counter runs up to.
-// flags: bit 0 = this entry journals the descriptor; bits 8-15 = OpKind; bits 16-23 = ranks;
+// flags: bit 0 = this entry journals the descriptor; bits 1-7 = element type; bits 8-15 = OpKind;
+// bits 16-23 = ranks;
 // bits 24-31 = mask of the ranks whose buffer a reduce entry stores to.
 struct CopyEnt {
   uint64_t src, dst, nbytes;
@@ -73,13 +71,14 @@ static_assert(sizeof(CopyArgs) <= 4096, "kernel argument block");
 struct CollEnt {
   uint64_t buf[kMaxBufs];
   uint64_t nbytes;
-  uint32_t slot, gen, nbuf, dtype;
+  uint32_t slot, gen, nbuf;
+  uint32_t chunk_bytes;  // per entry: the best chunk of a reduce entry depends on its number of ranks
   uint32_t world_id, world_epoch;  // journalled only
   uint32_t op_chunks, flags;
 };
 struct CollArgs {
   uint32_t n;
-  uint32_t chunk_shift;
+  uint32_t pad0;
   uint32_t first_chunk[kCollMax + 1];
   uint32_t pad;
   CollEnt e[kCollMax];
@@ -285,8 +284,8 @@ __global__ __launch_bounds__(kCopyWG) void mw_k_bcast(const CollArgs a, RingSlot
   const uint32_t slot = a.e[op].slot, gen = a.e[op].gen, nbuf = a.e[op].nbuf;
   const uint32_t ci = c - a.first_chunk[op];
   const uint32_t nchunks = a.e[op].op_chunks, flags = a.e[op].flags;
-  const uint64_t off = (uint64_t)ci << a.chunk_shift;
-  const uint64_t chunk = 1ull << a.chunk_shift;
+  const uint64_t chunk = a.e[op].chunk_bytes;
+  const uint64_t off = (uint64_t)ci * chunk;
   const uint64_t len = (nbytes - off < chunk) ? nbytes - off : chunk;
   rsrc_t dw[kMaxBufs - 1];
   uint64_t align = a.e[op].buf[0];
@@ -302,7 +301,7 @@ __global__ __launch_bounds__(kCopyWG) void mw_k_bcast(const CollArgs a, RingSlot
     for (int k = 0; k < kMaxBufs; ++k) d->buf[k] = (k < (int)nbuf) ? a.e[op].buf[k] : 0;
     d->nbytes = nbytes;
     d->kind = (flags >> 8) & 0xFFu;
-    d->dtype = a.e[op].dtype;
+    d->dtype = (flags >> 1) & 0x7Fu;
     d->nbuf = (flags >> 16) & 0xFFu;
     d->world_id = a.e[op].world_id;
     d->world_epoch = a.e[op].world_epoch;
@@ -367,7 +366,7 @@ struct Acc<true> {
 template <bool BF16, int N, bool ALL>
 __device__ __forceinline__ void reduce_vectors(const uint64_t* buf, uint64_t off, uint32_t len, uint32_t root,
                                                uint32_t nvec) {
-  constexpr int U = kReduceU;
+  constexpr int U = reduce_u(N);
   const uint32_t step = kReduceWG * U;
   rsrc_t w[N];
 #pragma unroll
@@ -511,12 +510,13 @@ __global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs a, RingS
   const uint32_t c = blockIdx.x;
   const int op = find_op(a.first_chunk, (int)a.n, c);
   const uint64_t nbytes = a.e[op].nbytes;
-  const uint32_t slot = a.e[op].slot, gen = a.e[op].gen, nbuf = a.e[op].nbuf, dtype = a.e[op].dtype;
+  const uint32_t slot = a.e[op].slot, gen = a.e[op].gen, nbuf = a.e[op].nbuf;
   const uint32_t ci = c - a.first_chunk[op];
   const uint32_t nchunks = a.e[op].op_chunks, flags = a.e[op].flags;
   const uint32_t wmask = flags >> 24;  // ranks whose buffer receives the sum (all of them, or the root only)
-  const uint64_t off = (uint64_t)ci << a.chunk_shift;
-  const uint64_t chunk = 1ull << a.chunk_shift;
+  const uint32_t dtype = (flags >> 1) & 0x7Fu;
+  const uint64_t chunk = a.e[op].chunk_bytes;
+  const uint64_t off = (uint64_t)ci * chunk;
   const uint64_t len = (nbytes - off < chunk) ? nbytes - off : chunk;
   const uint64_t* buf = a.e[op].buf;  // unused entries are zero
   uint64_t align = 0;
@@ -803,18 +803,25 @@ class HipDevice : public Device {
     return e;
   }
 
-  uint32_t pick_chunk_shift(uint32_t kind, uint64_t total_bytes) const {
-    if (cfg_.chunk_bytes) return floor_log2(cfg_.chunk_bytes);
-    // enough workgroups to fill 256 CUs several times over, chunks large enough to amortise
-    // the per-chunk completion protocol
-    // Copies peak at 128 KiB chunks (two passes of 1024 threads x 4 x 16 B): measured 6.44 TB/s of
-    // traffic on 8 x 512 MiB against 6.01 (64 KiB) and 6.34 (256 KiB).
-    // All-reduce peaks at 16 KiB per rank (one pass of 1024 threads x 16 B over every rank):
-    // 5.73 TB/s on 8 x (4 ranks x 64 MiB) against 5.29 (8 KiB / 32 KiB) and 4.77 (64 KiB).
-    const uint32_t lo = kind == kReduce ? 13 : 14;   // 8 KiB / 16 KiB
-    const uint32_t hi = kind == kReduce ? 14 : 17;   // 16 KiB / 128 KiB
-    uint32_t s = floor_log2(total_bytes / 2048 + 1);
-    return std::min(hi, std::max(lo, s));
+  // Chunk size of an entry with `nbuf` buffers in a launch of `total_bytes`: enough workgroups to fill
+  // 256 CUs several times over, chunks large enough to amortise the per-chunk completion protocol.
+  // Copies and fan-outs peak at 128 KiB chunks (two passes of 1024 threads x 4 x 16 B): measured 6.44 TB/s
+  // of traffic on 8 x 512 MiB against 6.01 (64 KiB) and 6.34 (256 KiB).
+  // All-reduce peaks where a workgroup's chunks of all ranks together come to 40-64 KiB, whatever the number
+  // of ranks (TB/s of traffic on 8 worlds x 256 MiB, by chunk per rank):
+  //   2 ranks 3.1 (8 KiB) 5.3 (16) 6.2 (24) 6.1 (32)     3 ranks 4.4 (8) 6.0 (16) 5.9 (32)
+  //   4 ranks 5.4 (8) 6.2 (12) 5.9 (16) 5.5 (32)          5 ranks 6.1 (8) 6.0 (12) 5.7 (16)
+  //   6 ranks 6.5 (8) 5.6 (16)    7 ranks 6.4 (8) 5.3 (16)    8 ranks 5.1 (4) 5.9 (8) 5.1 (16)
+  // A reduce to one root writes one buffer only and peaks at larger chunks (8 / 16 / 32 / 64 KiB):
+  //   2 ranks 2.4 / 4.3 / 6.2 / 6.0    4 ranks 3.6 / 5.8 / 6.3 / 5.6    5 ranks 4.2 / 6.1 / 6.1 / 5.6
+  //   6 ranks 4.6 / 6.3 / 6.0 / 5.5    8 ranks 5.2 / 6.1 / 5.7 / 5.5
+  uint32_t pick_chunk_bytes(uint32_t kind, uint64_t total_bytes, uint32_t nbuf, bool all_ranks_written) const {
+    if (cfg_.chunk_bytes) return cfg_.chunk_bytes;
+    const uint32_t fill = 1u << std::min(30u, floor_log2(total_bytes / 2048 + 1));
+    if (kind != kReduce) return std::min(128u << 10, std::max(16u << 10, fill));
+    const uint32_t best = !all_ranks_written ? (nbuf <= 5 ? 32u << 10 : 16u << 10)
+                          : nbuf <= 2 ? 32u << 10 : nbuf == 3 ? 16u << 10 : nbuf == 4 ? 12u << 10 : 8u << 10;
+    return std::min(best, std::max(8u << 10, fill));
   }
 
   struct Ent {  // one kernel entry of an operation
@@ -843,7 +850,7 @@ class HipDevice : public Device {
     e.world_epoch = o.world_epoch;
     e.group = group;
     const bool first = ents_.empty() || ents_.back().group != group;
-    e.flags = (first ? 1u : 0u) | (o.kind << 8) | (o.nbuf << 16) | (wmask << 24);
+    e.flags = (first ? 1u : 0u) | ((o.dtype & 0x7Fu) << 1) | (o.kind << 8) | (o.nbuf << 16) | (wmask << 24);
     ents_.push_back(e);
   }
 
@@ -904,12 +911,18 @@ class HipDevice : public Device {
     const int n = (int)ents_.size();
     uint64_t total_bytes = 0;
     for (const Ent& e : ents_) total_bytes += e.nbytes;
-    const uint32_t shift = pick_chunk_shift(kind, total_bytes);
-    // chunks per entry, and per operation (= run of entries with the same group)
+    // chunks per entry, and per operation (= run of entries with the same group); copies and fan-outs use
+    // one (power of two) size per launch
+    const uint32_t launch_chunk = pick_chunk_bytes(kind, total_bytes, 2, true);
     chunks_.resize((size_t)n);
+    chunk_bytes_.resize((size_t)n);
     uint64_t chunks = 0;
     for (int i = 0; i < n; ++i) {
-      chunks_[(size_t)i] = (uint32_t)((ents_[(size_t)i].nbytes + (1ull << shift) - 1) >> shift);
+      const Ent& e = ents_[(size_t)i];
+      const bool all_written = (e.flags >> 24) == (1u << e.nbuf) - 1u;
+      const uint32_t cb = kind == kReduce ? pick_chunk_bytes(kind, total_bytes, e.nbuf, all_written) : launch_chunk;
+      chunk_bytes_[(size_t)i] = cb;
+      chunks_[(size_t)i] = (uint32_t)((e.nbytes + cb - 1) / cb);
       chunks += chunks_[(size_t)i];
     }
     if (chunks == 0 || chunks > 0x7FFFFFFFull) return fail_inval();
@@ -931,7 +944,7 @@ class HipDevice : public Device {
     if (kind == kCopy) {
       CopyArgs& a = copy_args_;
       a.n = (uint32_t)n;
-      a.chunk_shift = shift;
+      a.chunk_shift = floor_log2(launch_chunk);
       for (int i = 0; i < n; ++i) {
         const Ent& e = ents_[(size_t)i];
         a.first_chunk[i] = at;
@@ -944,7 +957,6 @@ class HipDevice : public Device {
     } else {
       CollArgs& a = coll_args_;
       a.n = (uint32_t)n;
-      a.chunk_shift = shift;
       for (int i = 0; i < n; ++i) {
         const Ent& e = ents_[(size_t)i];
         a.first_chunk[i] = at;
@@ -955,7 +967,7 @@ class HipDevice : public Device {
         c.slot = e.slot;
         c.gen = e.gen;
         c.nbuf = e.nbuf;
-        c.dtype = e.dtype;
+        c.chunk_bytes = chunk_bytes_[(size_t)i];
         c.world_id = e.world_id;
         c.world_epoch = e.world_epoch;
         c.op_chunks = op_chunks_[(size_t)i];
@@ -1015,7 +1027,7 @@ class HipDevice : public Device {
   ProfAcc acc_[kNumKinds];
   std::vector<Ent> ents_, one_;
   uint8_t* launched_ = nullptr;  // the current launch() call's per-operation result array
-  std::vector<uint32_t> chunks_, op_chunks_;
+  std::vector<uint32_t> chunks_, op_chunks_, chunk_bytes_;
   CopyArgs copy_args_{};
   CollArgs coll_args_{};
 };
