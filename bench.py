@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--reps", type=int, default=5, help="repetitions of the multi-/single-world comparison")
+    ap.add_argument("--reps", type=int, default=10, help="repetitions of the multi-/single-world comparison (the paper's Sec. 4.3 averages 10)")
     ap.add_argument("--cpu-steps", type=int, default=24, help="steps of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", type=int, default=0,
@@ -271,6 +271,8 @@ def main_config2(args, torch, mw, dev):
         "single_world_GBps": round(mean(sw_rates), 1) if args.reps else None,
         "multi_world_GBps_mean": round(mean(mw_rates), 1) if args.reps else None,
         "loss_vs_single_world_pct": round(loss_pct, 3) if args.reps else None,
+        "single_world_GBps_min_max": [round(min(sw_rates), 1), round(max(sw_rates), 1)] if args.reps else None,
+        "multi_world_GBps_min_max": [round(min(mw_rates), 1), round(max(mw_rates), 1)] if args.reps else None,
         "overhead_reps": args.reps,
         "achievable": ceiling,
         "roofline": {
