@@ -49,6 +49,8 @@ def parse():
                     help="config2 (default) is the headline workload; the others are measured the same way")
     ap.add_argument("--abort-step", type=int, default=100, help="config4: step before which worker 7 is aborted")
     ap.add_argument("--ops", type=int, default=10_000, help="config5: operations in the trace")
+    ap.add_argument("--window", type=int, default=32, help="config5: operations per window")
+    ap.add_argument("--depth", type=int, default=2, help="config5: windows in flight (window x depth <= 64)")
     ap.add_argument("--chunk-bytes", type=int, default=0, help="pin the kernels' chunk size (0 = chosen per launch)")
     ap.add_argument("--reduce-lds", type=int, default=0, help="config3: 1 = LDS-staged all-reduce kernel")
     ap.add_argument("--shape", type=int, nargs=3, default=list(SHAPE), help=argparse.SUPPRESS)
@@ -586,16 +588,17 @@ def run_config1(torch, mw, dev, reps):
     }
 
 
-def run_config5(torch, mw, dev, n_ops, reps):
+def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
     """Mixed scale-out: the seeded 10 000-operation trace (64 worlds of 2-4 over 32 workers, 70/20/10 %
-    p2p / broadcast / all-reduce, 4 KiB - 64 MiB, fp32/bf16, three worker aborts), <= 64 outstanding (two
-    half-windows of 32 in flight).
+    p2p / broadcast / all-reduce, 4 KiB - 64 MiB, fp32/bf16, three worker aborts), <= 64 outstanding (`depth`
+    windows of `window` operations in flight).
     Buffers are slices of one pre-filled slab so that no initialisation runs inside the timed region."""
     import workloads
 
-    t = workloads.config5(n_ops=n_ops, window=32)  # two half-windows of 32 in flight: <= 64 outstanding
+    assert window * depth <= 64
+    t = workloads.config5(n_ops=n_ops, window=window)
     slab_bytes = 40 << 30
-    half = slab_bytes // 2
+    half = slab_bytes // depth // 256 * 256
     slab = torch.empty(slab_bytes, dtype=torch.uint8, device=dev)
     g = torch.Generator(device=dev)
     g.manual_seed(5)
@@ -612,8 +615,8 @@ def run_config5(torch, mw, dev, n_ops, reps):
             if op.kind in kind_of:
                 if op.buf not in where:
                     nb = (t.bufs[op.buf].nbytes + 255) & ~255
-                    assert off + nb <= half, "slab too small for a half-window"
-                    where[op.buf] = (seg % 2) * half + off  # consecutive half-windows use different halves
+                    assert off + nb <= half, "slab too small for a window"
+                    where[op.buf] = (seg % depth) * half + off  # windows in flight together use different parts
                     off += nb
                 posts.append((kind_of[op.kind], world_base + op.world, op.a, max(op.b, 0), base + where[op.buf], op.count,
                               mw.DTYPES[op.dtype], mw.STREAM_NONE))
@@ -650,12 +653,14 @@ def run_config5(torch, mw, dev, n_ops, reps):
                 live.append(x)
             elif kind == "abort":
                 mw.mw_worker_abort(x)
-            else:  # end of a half-window: launch it, then wait for the one before it
+            else:  # end of a window: launch it, then wait until fewer than `depth` are in flight
                 mw.mw_flush()
-                cur = [mw.PollSet([h for h in pb.handles if h]) for pb in live]
-                drain(prev)
-                prev, live = cur, []
-        drain(prev)
+                prev.append([mw.PollSet([h for h in pb.handles if h]) for pb in live])
+                live = []
+                while len(prev) >= depth:
+                    drain(prev.pop(0))
+        for sets in prev:
+            drain(sets)
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
@@ -684,7 +689,7 @@ def run_config5(torch, mw, dev, n_ops, reps):
         "value": round(payload / secs / 1e9, 1), "ms_per_step": round(secs * 1e3, 3), "steps": len(times),
         "config": {"workload": f"config 5: mixed scale-out, 64 worlds of 2-4 over 32 workers, {n_ops} operations 70/20/10 % "
                                "send-recv / broadcast / all-reduce, 4 KiB - 64 MiB log-uniform, fp32/bf16, 3 worker "
-                               "aborts, <= 64 outstanding", "worlds": 64, "payload_dtype": "f32/bf16"},
+                               f"aborts, {depth} windows of {window} operations in flight", "worlds": 64, "payload_dtype": "f32/bf16"},
         "payload_bytes_done": payload, "algorithmic_bytes": alg,
         "hbm_traffic_GBps": round(alg / secs / 1e9, 1), "pct_of_hbm_peak": round(alg / secs / 1e9 / HBM_PEAK_GBPS * 100, 2),
         "roofline": None,
@@ -963,7 +968,7 @@ def main():
     elif args.workload == "online":
         res = run_online(torch, mw, dev, args.reps)
     else:
-        res = run_config5(torch, mw, dev, args.ops, args.reps)
+        res = run_config5(torch, mw, dev, args.ops, args.reps, args.window, args.depth)
     mw.mw_shutdown()
     out = {"metric": METRIC, "value": res.pop("value"), "unit": "GB/s", "n_gpus": 1, "steps": res.pop("steps"),
            "warmup": args.warmup, "ms_per_step": res.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak",

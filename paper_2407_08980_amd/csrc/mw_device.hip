@@ -817,7 +817,14 @@ class HipDevice : public Device {
   //   6 ranks 4.6 / 6.3 / 6.0 / 5.5    8 ranks 5.2 / 6.1 / 5.7 / 5.5
   uint32_t pick_chunk_bytes(uint32_t kind, uint64_t total_bytes, uint32_t nbuf, bool all_ranks_written) const {
     if (cfg_.chunk_bytes) return cfg_.chunk_bytes;
-    const uint32_t fill = 1u << std::min(30u, floor_log2(total_bytes / 2048 + 1));
+    // Smaller launches take smaller chunks, down to where the launch still has ~512 (copies, fan-outs) or
+    // ~256 (reduce) workgroups.  Kernel time by chunk size, 8 equal messages per launch:
+    //   copy, 32 MiB of payload      16 KiB 18.6 us, 32 KiB 16.8, 64 KiB 14.9, 128 KiB 15.0
+    //   copy, 8 MiB                  16 KiB  7.2 us, 32 KiB  7.1, 64 KiB  7.4, 128 KiB  8.4
+    //   all-reduce, 2 x 16 MiB       8 KiB 22.9 us, 16 KiB 17.6, 32 KiB 17.7
+    //   all-reduce, 2 x 2 MiB        8 KiB  7.7 us, 16 KiB  8.3, 32 KiB  9.1
+    const uint64_t groups = kind == kReduce ? 256 : 512;
+    const uint32_t fill = 1u << std::min(30u, floor_log2(total_bytes / groups + 1));
     if (kind != kReduce) return std::min(128u << 10, std::max(16u << 10, fill));
     const uint32_t best = !all_ranks_written ? (nbuf <= 5 ? 32u << 10 : 16u << 10)
                           : nbuf <= 2 ? 32u << 10 : nbuf == 3 ? 16u << 10 : nbuf == 4 ? 12u << 10 : 8u << 10;
