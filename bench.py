@@ -30,8 +30,8 @@ POOL_K = 4
 # HBM bytes per mw_k_copy launch of this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (summary in
 # profiles/mw_k_copy_config2_hbm_counters.txt).  Valid only for the kernel source it was taken with: once
 # csrc/mw_device.hip changes, `traffic` is reported as null until the counters are taken again.
-PMC_TRAFFIC = {"sha256": "2b5acd6a54e59884cc296a9a4a4aecb2f6b0bf06c7b397dd7072e4b0a4b91730",
-               "bytes_per_launch": 8590981323}
+PMC_TRAFFIC = {"sha256": "af912d928346216c1f0eb6068b23b64e1a778b645506887520f52fe7736dc9be",
+               "bytes_per_launch": 8590961707}
 
 
 def parse():
@@ -818,7 +818,7 @@ def run_sweep(torch, mw, dev, reps):
             pbm, pbs = batch(True), batch(False)
             run(pbm), run(pbs)
             tm, ts = [], []
-            for _ in range(max(reps, 1) * (10 if count < 1_000_000 else 2)):  # a run of small messages lasts 1-15 ms
+            for _ in range(max(reps, 1) * 10):  # one run lasts 1-10 ms
                 ts.append(run(pbs))
                 tm.append(run(pbm))
             for k in range(senders):

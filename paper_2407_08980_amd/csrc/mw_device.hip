@@ -1015,13 +1015,15 @@ class HipDevice : public Device {
   uint32_t* flags_dev_ = nullptr;
   // kLanes streams per kernel kind.  Back-to-back kernels on one stream are separated by ~6 us of
   // release / acquire and dispatch; a launch on a stream that has gone idle costs ~10 us to get going.
-  // So: large launches (>= 512 MiB of traffic) go one after the other on lane 0 (two bandwidth-bound
-  // kernels side by side measured -1 %); medium launches alternate between lanes 1 and 2, so that the
+  // So: large launches (>= 4 GiB of traffic, kernels of >~0.7 ms) go one after the other on lane 0 (two
+  // bandwidth-bound kernels side by side measured -1 %, more than the boundary costs them; at 0.8 GiB per
+  // launch it is the other way round: two worlds streaming 4 MB tensors together moved 2.91 TB/s one after
+  // the other and 3.15 alternating); medium launches alternate between lanes 1 and 2, so that the
   // boundary of one is hidden behind the other (the 4 x 4-rank all-reduce iteration went from 19.2 to
   // 12.4 us, windows of 4 MB messages gained 8 %); small launches (kernels of a few us) stay on lane 1,
   // where alternating measured 15-25 % slower.
   static constexpr int kLanes = 3;
-  static constexpr uint64_t kLargeLaunchBytes = 512ull << 20;  // of traffic (bytes x buffers) per launch
+  static constexpr uint64_t kLargeLaunchBytes = 4096ull << 20;  // of traffic (bytes x buffers) per launch
   hipStream_t lanes_[kNumKinds][kLanes] = {};
   uint32_t lane_cursor_[kNumKinds] = {};
   hipStream_t data_[kNumKinds] = {};  // the lane each kind uses in the current launch() call
