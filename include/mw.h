@@ -236,6 +236,11 @@ int mw_handle_capacity(void);
 int mw_last_hip_error(void);
 const char* mw_strerror(int err);
 
+/* Identity of the sources this library was compiled from: the hex SHA-256 (first 16 digits) over the files
+ * of csrc/ and this header, passed in by the build script; "unknown" for a build made by hand.  The Python
+ * binding refuses a library whose identity is not that of the sources beside it.  Static storage. */
+const char* mw_build_id(void);
+
 /* Per-kernel timing with HIP events on the library's own stream.  mw_profile_enable(1) starts
  * bracketing every data-kernel launch with events; mw_profile_read sums the finished launches of
  * kernel kind `kind` (0 copy incl. gather / scatter segments, 1 fan-out: broadcast and all-gather, 2 reduce:

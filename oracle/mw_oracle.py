@@ -100,9 +100,10 @@ def _as_bytes(buf):
 def _values_f64(raw, count, dtype):
     """Read `count` elements of `dtype` from a byte buffer as float64."""
     n = count * _ITEMSIZE[dtype]
-    if dtype == F32:
-        return raw[:n].view(np.float32).astype(np.float64)
-    return bf16_bits_to_f32(raw[:n].view(np.uint16)).astype(np.float64)
+    with np.errstate(invalid="ignore"):  # widening a signalling NaN raises the flag; the value is still a NaN
+        if dtype == F32:
+            return raw[:n].view(np.float32).astype(np.float64)
+        return bf16_bits_to_f32(raw[:n].view(np.uint16)).astype(np.float64)
 
 
 # ---------------------------------------------------------------------------

@@ -31,7 +31,7 @@ SYMBOLS = [
     "mw_config_set", "mw_config_get", "mw_handle_capacity", "mw_last_hip_error", "mw_strerror",
     "mw_profile_enable", "mw_profile_read", "mw_debug_ring_read", "mw_debug_arena_hash", "mw_heartbeat",
     "mw_heartbeat_at", "mw_watchdog_start", "mw_watchdog_stop", "mw_watchdog_check_at", "mw_worker_state",
-    "mw_heartbeat_epoch",
+    "mw_heartbeat_epoch", "mw_build_id",
 ]
 
 
@@ -83,6 +83,8 @@ def declare(lib):
     lib.mw_last_hip_error.argtypes = []
     lib.mw_strerror.argtypes = [i]
     lib.mw_strerror.restype = C.c_char_p
+    lib.mw_build_id.argtypes = []
+    lib.mw_build_id.restype = C.c_char_p
     lib.mw_profile_enable.argtypes = [i]
     lib.mw_profile_read.argtypes = [i, u64p, C.POINTER(C.c_double), u64p]
     lib.mw_debug_ring_read.argtypes = [i, vp, sz]
@@ -106,7 +108,18 @@ def lib():
             raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2407_08980_amd.build` "
                                "(there is no fallback path)")
         _lib = declare(C.CDLL(LIB_PATH))
+        check_build(_lib, LIB_PATH)
     return _lib
+
+
+def check_build(handle, path):
+    """A library compiled from other sources than the ones beside it must not be measured or tested."""
+    from . import build
+
+    have, want = handle.mw_build_id().decode(), build.source_id()
+    if have != want:
+        raise RuntimeError(f"{path} was built from other sources (library {have}, sources {want}): run "
+                           "`python -m paper_2407_08980_amd.build`")
 
 
 def use_library(handle):

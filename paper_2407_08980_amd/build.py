@@ -24,6 +24,23 @@ HIP_FLAGS = [
 ]
 
 
+def source_id():
+    """First 16 hex digits of the SHA-256 over the native sources and the public header, in name order."""
+    import hashlib
+
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".cpp", ".hpp")))
+    files.append(os.path.join(os.path.dirname(HERE), "include", "mw.h"))
+    for f in files:
+        h.update(os.path.basename(f).encode() + b"\0")
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def _build_id_flag():
+    return '-DMW_BUILD_ID="%s"' % source_id()
+
+
 def _run(cmd):
     p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in p.stdout.splitlines() if "is not a recognized feature for this target" not in l)
@@ -34,12 +51,38 @@ def _run(cmd):
 
 def build_product():
     srcs = [os.path.join(CSRC, "mw_device.hip"), os.path.join(CSRC, "mw_host.cpp")]
-    return _run([HIPCC] + HIP_FLAGS + srcs + ["-o", LIB])
+    return _run([HIPCC] + HIP_FLAGS + [_build_id_flag()] + srcs + ["-o", LIB])
 
 
 def build_hostcheck():
     srcs = [os.path.join(CSRC, "mw_host.cpp"), os.path.join(CSRC, "mw_device_null.cpp")]
-    return _run(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", "-Wall"] + srcs + ["-o", LIB_HOSTCHECK])
+    return _run(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", "-Wall", _build_id_flag()] + srcs + ["-o", LIB_HOSTCHECK])
+
+
+def library_id(path):
+    """Build identity stored in a built library, or None if it cannot be read."""
+    import ctypes
+
+    try:
+        lib = ctypes.CDLL(path)
+        lib.mw_build_id.restype = ctypes.c_char_p
+        return lib.mw_build_id().decode()
+    except (OSError, AttributeError):
+        return None
+
+
+def fresh_hostcheck():
+    """Path of the host-check library, rebuilt first if it is missing or was made from other sources.  (A stale
+    copy must be replaced before this process loads it: a loaded library is not reloaded from a new file.)"""
+    import multiprocessing as mp
+
+    stale = not os.path.exists(LIB_HOSTCHECK)
+    if not stale:
+        with mp.get_context("spawn").Pool(1) as pool:  # read the id in a child so the old file is never mapped here
+            stale = pool.apply(library_id, (LIB_HOSTCHECK,)) != source_id()
+    if stale:
+        build_hostcheck()
+    return LIB_HOSTCHECK
 
 
 def build_all():

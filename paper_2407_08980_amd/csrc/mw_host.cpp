@@ -914,6 +914,11 @@ int mw_last_hip_error(void) {
   return g_ctx ? g_ctx->dev->last_hip_error() : 0;
 }
 
+#ifndef MW_BUILD_ID
+#define MW_BUILD_ID "unknown"
+#endif
+const char* mw_build_id(void) { return MW_BUILD_ID; }
+
 const char* mw_strerror(int err) {
   switch (err) {
     case MW_OK: return "ok";

@@ -20,9 +20,7 @@ from helpers import ROOT
 
 @pytest.fixture(scope="module")
 def hostlib():
-    if not os.path.exists(mwbuild.LIB_HOSTCHECK):
-        mwbuild.build_hostcheck()
-    lib = C.CDLL(mwbuild.LIB_HOSTCHECK)
+    lib = C.CDLL(mwbuild.fresh_hostcheck())
     lib.mwt_log_entry.argtypes = [C.c_int, C.POINTER(C.c_uint64)]
     old = mw._lib
     mw.use_library(lib)
@@ -44,9 +42,16 @@ def log_entry(lib, i):
                 gen=out[13], world=out[14], epoch=out[15], launch=out[16], root=out[17], buf_hi=list(out[18:26]))
 
 
+def _id_in_child(path):
+    import multiprocessing as mp
+
+    with mp.get_context("spawn").Pool(1) as pool:  # a library mapped here would not be reloaded after a rebuild
+        return pool.apply(mwbuild.library_id, (path,))
+
+
 def test_header_symbols_are_exported_by_the_product_library():
-    if not os.path.exists(mw.LIB_PATH):
-        mwbuild.build_product()
+    if not os.path.exists(mw.LIB_PATH) or _id_in_child(mw.LIB_PATH) != mwbuild.source_id():
+        mwbuild.build_product()  # missing, or compiled from other sources than the ones in the tree
     text = open(os.path.join(ROOT, "include", "mw.h")).read()
     declared = set(re.findall(r"^\s*(?:int|long|const char\*)\s+(mw_\w+)\s*\(", text, flags=re.M))
     assert {"mw_world_create", "mw_send", "mw_recv", "mw_broadcast", "mw_allreduce_sum", "mw_poll",
@@ -55,6 +60,8 @@ def test_header_symbols_are_exported_by_the_product_library():
     missing = [s for s in sorted(declared) if not hasattr(lib, s)]
     assert not missing, missing
     assert declared == set(mw.SYMBOLS), declared ^ set(mw.SYMBOLS)
+    lib.mw_build_id.restype = C.c_char_p
+    assert lib.mw_build_id().decode() == mwbuild.source_id()
     # without a GPU the library must refuse loudly, not fall back
     import torch
 

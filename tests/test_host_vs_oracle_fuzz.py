@@ -19,9 +19,7 @@ STATE = {mw.MW_DONE: DONE, mw.MW_PENDING: PENDING, mw.MW_BROKEN: BROKEN, mw.MW_E
 
 @pytest.fixture(scope="module")
 def hostlib():
-    if not os.path.exists(mwbuild.LIB_HOSTCHECK):
-        mwbuild.build_hostcheck()
-    lib = C.CDLL(mwbuild.LIB_HOSTCHECK)
+    lib = C.CDLL(mwbuild.fresh_hostcheck())
     old = mw._lib
     mw.use_library(lib)
     yield lib

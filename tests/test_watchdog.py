@@ -22,9 +22,7 @@ from paper_2407_08980_amd import build as mwbuild
 
 @pytest.fixture(scope="module")
 def hostlib():
-    if not os.path.exists(mwbuild.LIB_HOSTCHECK):
-        mwbuild.build_hostcheck()
-    lib = C.CDLL(mwbuild.LIB_HOSTCHECK)
+    lib = C.CDLL(mwbuild.fresh_hostcheck())
     old = mw._lib
     mw.use_library(lib)
     yield lib
