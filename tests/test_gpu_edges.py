@@ -349,6 +349,49 @@ def test_ring_journal_header_and_isolation_across_abort(torch, mw):
     assert e.value.code == mw.MW_EBROKEN
 
 
+@pytest.mark.parametrize("n", [2, 3, 4, 5, 6, 8])
+def test_large_reductions_in_every_chunk_size_the_library_chooses(torch, mw, n):
+    """The chunk of a reduce entry depends on the number of ranks and on who is written (all-reduce 32 / 16 /
+    12 / 8 KiB, reduce to a root 32 / 16 KiB; two vectors per thread for 2 ranks).  Payloads here are large
+    enough for the largest choice, with a ragged tail; the journal in the world's ring tells which was taken."""
+    mw.mw_world_create(0, list(range(n)))
+    count = (9 << 20) // 4 + 1237  # 9 MiB and a tail per rank: several hundred chunks of any size
+    rng = np.random.default_rng(900 + n)
+    seen = set()
+    for dtype, root in (("f32", None), ("bf16", None), ("f32", n - 1)):
+        c = count if dtype == "f32" else 2 * count + 3
+        xs = [rng.uniform(-1, 1, c).astype(np.float32) for _ in range(n)]
+        host = [x.view(np.uint8) if dtype == "f32" else oracle.f32_to_bf16_bits(x).view(np.uint8) for x in xs]
+        dev = [dev_bytes(torch, host[r]) for r in range(n)]
+        if root is None:
+            hs = [mw.mw_allreduce_sum(0, r, dev[r][1].data_ptr(), c, mw.DTYPES[dtype]) for r in range(n)]
+        else:
+            hs = [mw.mw_reduce_sum(0, r, root, dev[r][1].data_ptr(), c, mw.DTYPES[dtype]) for r in range(n)]
+        assert wait(mw, hs) == [mw.MW_DONE] * n
+        s, sabs = oracle.allreduce_sum_f64(host, c, dtype)
+        ordered = oracle.allreduce_sum_ordered(host, c, dtype)
+        for r in range(n):
+            got = dev[r][1].cpu().numpy()
+            if root is None or r == root:
+                ok, worst = oracle.allreduce_within_tolerance(got, s, sabs, c, dtype)
+                assert ok, (n, dtype, root, r, worst)
+                assert np.array_equal(got, ordered), (n, dtype, root, r)
+            else:
+                assert np.array_equal(got, host[r]), "a non-root buffer was written"
+            base = dev[r][0].cpu().numpy()
+            assert np.all(base[host[r].size:] == 0x5A)  # nothing past the end
+        raw = mw.mw_debug_ring_read(0)
+        mine = [f for f in (_slot_fields(raw, i) for i in range(128))
+                if f["gen"] and f["bufs"][0] == dev[0][1].data_ptr() and f["nbytes"] == host[0].size
+                and f["kind"] == (2 if root is None else 3) and f["dtype"] == mw.DTYPES[dtype]]
+        last = max(mine, key=lambda f: f["gen"])
+        assert last["nchunks"] * last["chunk"] >= host[0].size > (last["nchunks"] - 1) * last["chunk"]
+        seen.add((root is None, last["chunk"]))
+    want_all = {2: 32, 3: 16, 4: 12}.get(n, 8) << 10
+    want_root = (32 if n <= 5 else 16) << 10
+    assert seen == {(True, want_all), (False, want_root)}, seen
+
+
 def test_watchdog_cleans_up_a_silent_worker_while_others_stream(torch, mw):
     """Silent failure on the GPU path: worker 2 stops reporting; the watchdog thread breaks its world only,
     the transfer it had already been matched for is delivered, the other world keeps moving data."""
