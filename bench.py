@@ -134,6 +134,17 @@ class Workload:
                     raise RuntimeError(f"world {w} step {s}: destination differs from source")
 
 
+def calibration_copies(torch, dev, n):
+    """n plain 1 GiB device copies: the known-size kernel that hardware counters of a profiling run are scaled by."""
+    if n:
+        a = torch.full((1 << 30,), 3, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(n):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
+
 def achievable_ceiling(torch, mw, wl, reps=20):
     """What one GPU gives a plain copy of one message, for context beside the 8 TB/s peak: the runtime's own
     device-to-device memcpy and a single message through the library alone on the GPU (read + write bytes / time)."""
@@ -211,13 +222,7 @@ def main_config2(args, torch, mw, dev):
     multi = (list(range(N_WORLDS)), [(0, 1)] * N_WORLDS)
     single = ([SINGLE] * N_WORLDS, [(2 * w, 2 * w + 1) for w in range(N_WORLDS)])
 
-    if args.calibrate:
-        a = torch.full((1 << 30,), 3, dtype=torch.uint8, device=dev)
-        b = torch.empty_like(a)
-        for _ in range(args.calibrate):
-            b.copy_(a)
-        torch.cuda.synchronize()
-        del a, b
+    calibration_copies(torch, dev, args.calibrate)
     K, W = args.steps, args.warmup
     wl.run(W, *multi)
     mw.mw_profile_enable(True)
@@ -955,6 +960,7 @@ def main():
     if args.workload == "config2":
         return main_config2(args, torch, mw, dev)
     mw.mw_init(0, 64)
+    calibration_copies(torch, dev, args.calibrate)
     if args.workload == "config4":
         res = run_config4(torch, mw, dev, args.steps if args.steps != 50 else 300, args.abort_step, args.reps)
     elif args.workload == "config3":
