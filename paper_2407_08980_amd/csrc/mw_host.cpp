@@ -628,7 +628,16 @@ int mw_world_create(int world_id, const int* worker_ids, int n_ranks) {
     return rc;
   }
   uint32_t wi = (uint32_t)c.worlds.size();
-  for (int i = 0; i < n_ranks; ++i) c.worlds_of_worker[(size_t)worker_ids[i]].push_back(wi);
+  for (int i = 0; i < n_ranks; ++i) {
+    // A worker that keeps joining new worlds as old ones break (Sec. 3.1 recovery) must not pay for its
+    // history on every abort: drop the broken worlds from its list before adding the new one.
+    std::vector<uint32_t>& mine = c.worlds_of_worker[(size_t)worker_ids[i]];
+    size_t k = 0;
+    for (uint32_t x : mine)
+      if (c.worlds[x]->state != MW_BROKEN) mine[k++] = x;
+    mine.resize(k);
+    mine.push_back(wi);
+  }
   c.world_of_id.emplace(world_id, wi);
   c.worlds.push_back(std::move(w));
   return MW_OK;

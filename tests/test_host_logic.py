@@ -450,3 +450,30 @@ def test_per_operation_host_cost_does_not_grow_with_the_number_of_worlds(hostlib
 
     few, many = cost(4), cost(1000)
     assert many < 1.6 * few, f"{few * 1e9:.0f} ns per message with 4 worlds, {many * 1e9:.0f} ns with 1000"
+
+
+def test_worlds_a_worker_has_left_cost_nothing_later(hostlib):
+    """Elastic recovery (Sec. 3.1): a worker rejoins through new worlds again and again.  Aborting the worker
+    after 20 000 such generations must cost what it costs after 20."""
+    import time
+
+    mw.mw_config_set("max_rings", 8)
+    mw.mw_init(0, 4)
+    try:
+        def generation(first_id, n):
+            t0 = time.perf_counter()
+            for i in range(n):
+                mw.mw_world_create(first_id + i, [0, 1])
+                h = mw.mw_recv(first_id + i, 0, 1, 0x1000, 8, mw.MW_F32, mw.STREAM_NONE)
+                mw.mw_worker_abort(1)
+                assert mw.mw_poll(h) == mw.MW_BROKEN
+                assert mw.mw_world_state(first_id + i) == mw.MW_BROKEN
+            return (time.perf_counter() - t0) / n
+
+        early = generation(0, 200)
+        generation(1000, 20000)
+        late = generation(100000, 200)
+        assert late < 3 * early, f"{early * 1e6:.1f} us per generation at first, {late * 1e6:.1f} us after 20 000"
+    finally:
+        mw.mw_shutdown()
+        mw.mw_config_set("max_rings", 1024)
