@@ -614,17 +614,29 @@ def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
     base = slab.data_ptr()
     kind_of = {"send": mw.POST_SEND, "recv": mw.POST_RECV, "bcast": mw.POST_BROADCAST, "allreduce": mw.POST_ALLREDUCE_SUM}
 
-    def segments(world_base):
+    members = t.meta["members"]
+
+    def segments(world_base, p2p_only=False, single=False):
+        """Posts of the trace, cut at its window ends.  p2p_only: the send/recv subset without the aborts (what
+        the single-world comparison runs); single: every message goes through the one world `world_base`, whose
+        ranks are the worker ids."""
         segs, posts, off, where, seg = [], [], 0, {}, 0
         for op in t.ops:
+            if p2p_only and op.kind not in ("send", "recv", "wait"):
+                continue
             if op.kind in kind_of:
                 if op.buf not in where:
                     nb = (t.bufs[op.buf].nbytes + 255) & ~255
                     assert off + nb <= half, "slab too small for a window"
                     where[op.buf] = (seg % depth) * half + off  # windows in flight together use different parts
                     off += nb
-                posts.append((kind_of[op.kind], world_base + op.world, op.a, max(op.b, 0), base + where[op.buf], op.count,
-                              mw.DTYPES[op.dtype], mw.STREAM_NONE))
+                if single:
+                    m = members[op.world]
+                    posts.append((kind_of[op.kind], world_base, m[op.a], m[op.b], base + where[op.buf], op.count,
+                                  mw.DTYPES[op.dtype], mw.STREAM_NONE))
+                else:
+                    posts.append((kind_of[op.kind], world_base + op.world, op.a, max(op.b, 0), base + where[op.buf],
+                                  op.count, mw.DTYPES[op.dtype], mw.STREAM_NONE))
             elif op.kind == "abort_worker":
                 if posts:
                     segs.append(("post", mw.PostBatch(posts)))
@@ -644,11 +656,14 @@ def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
                 while ps.poll():
                     pass
 
-    def run(world_base):
-        for op in t.ops:
-            if op.kind == "create":
-                mw.mw_world_create(world_base + op.world, list(op.members))
-        segs = segments(world_base)
+    def run(world_base, p2p_only=False, single=False):
+        if single:
+            mw.mw_world_create(world_base, list(range(t.n_workers)))
+        else:
+            for op in t.ops:
+                if op.kind == "create":
+                    mw.mw_world_create(world_base + op.world, list(op.members))
+        segs = segments(world_base, p2p_only, single)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         live, prev = [], []
@@ -667,11 +682,13 @@ def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
         for sets in prev:
             drain(sets)
         torch.cuda.synchronize()
-        return time.perf_counter() - t0
+        secs = time.perf_counter() - t0
+        for wid in ([world_base] if single else [world_base + op.world for op in t.ops if op.kind == "create"]):
+            mw.mw_world_abort(wid)  # the pass is over: its rings go back to the arena
+        return secs
 
     # payload of the operations that complete: everything posted to a world that is still alive
     dead, payload, alg = set(), 0, 0
-    members = t.meta["members"]
     for op in t.ops:
         if op.kind == "abort_worker":
             dead.add(op.a)
@@ -690,6 +707,13 @@ def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
     run(10_000)  # warm-up (worker aborts only break this pass's worlds)
     times = [run(10_000 * (i + 2)) for i in range(max(reps, 1))]
     secs = sum(times) / len(times)
+    # single-world comparison on the send/recv subset (collectives change meaning in a bigger world, and one
+    # worker abort would end the single world): the same messages in the same order, no aborts on either side
+    p2p_payload = sum(op.count * (4 if op.dtype == "f32" else 2) for op in t.ops if op.kind == "recv")
+    sw_t, mw_t = [], []
+    for i in range(reps):
+        sw_t.append(run(1_000_000 + i, p2p_only=True, single=True))
+        mw_t.append(run(2_000_000 + 10_000 * i, p2p_only=True))
     return {
         "value": round(payload / secs / 1e9, 1), "ms_per_step": round(secs * 1e3, 3), "steps": len(times),
         "config": {"workload": f"config 5: mixed scale-out, 64 worlds of 2-4 over 32 workers, {n_ops} operations 70/20/10 % "
@@ -697,6 +721,9 @@ def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
                                f"aborts, {depth} windows of {window} operations in flight", "worlds": 64, "payload_dtype": "f32/bf16"},
         "payload_bytes_done": payload, "algorithmic_bytes": alg,
         "hbm_traffic_GBps": round(alg / secs / 1e9, 1), "pct_of_hbm_peak": round(alg / secs / 1e9 / HBM_PEAK_GBPS * 100, 2),
+        "p2p_subset_single_world_GBps": round(p2p_payload / (sum(sw_t) / len(sw_t)) / 1e9, 1) if reps else None,
+        "p2p_subset_multi_world_GBps": round(p2p_payload / (sum(mw_t) / len(mw_t)) / 1e9, 1) if reps else None,
+        "loss_vs_single_world_pct": round((1 - (sum(sw_t) / len(sw_t)) / (sum(mw_t) / len(mw_t))) * 100, 3) if reps else None,
         "roofline": None,
     }
 
