@@ -470,9 +470,9 @@ def test_worlds_a_worker_has_left_cost_nothing_later(hostlib):
                 assert mw.mw_world_state(first_id + i) == mw.MW_BROKEN
             return (time.perf_counter() - t0) / n
 
-        early = generation(0, 200)
+        early = min(generation(200 * k, 200) for k in range(3))  # best of three: robust on a busy host
         generation(1000, 20000)
-        late = generation(100000, 200)
+        late = min(generation(100000 + 200 * k, 200) for k in range(3))
         assert late < 3 * early, f"{early * 1e6:.1f} us per generation at first, {late * 1e6:.1f} us after 20 000"
     finally:
         mw.mw_shutdown()
