@@ -140,6 +140,17 @@ def test_sendrecv_fifo_order_per_pair_and_independence_across_pairs():
     assert not other_dst.any()
     h = o.post_recv(0, 2, 0, other_dst, 2, F32)
     assert o.status(h) == DONE and np.array_equal(other_dst, other_src)
+    # sends of another pair and of the opposite direction, posted EARLIER, are not what a recv of (1 -> 0) gets
+    o = WorldOracle(3)
+    o.create(0, (0, 1, 2))
+    x, y, a = rand_bytes(8, 11), rand_bytes(8, 12), rand_bytes(8, 13)
+    hx = o.post_send(0, 2, 0, x, 2, F32)
+    hy = o.post_send(0, 0, 1, y, 2, F32)
+    da = np.zeros(8, dtype=np.uint8)
+    hr = o.post_recv(0, 1, 0, da, 2, F32)
+    assert [o.status(h) for h in (hx, hy, hr)] == [PENDING] * 3 and not da.any()
+    ha = o.post_send(0, 1, 0, a, 2, F32)
+    assert [o.status(h) for h in (hx, hy, hr, ha)] == [PENDING, PENDING, DONE, DONE] and np.array_equal(da, a)
 
 
 def test_sendrecv_same_pair_in_two_worlds_does_not_cross():

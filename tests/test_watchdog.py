@@ -57,6 +57,13 @@ def test_oracle_watchdog_paper_numbers():
         o.create(9, (0, 2))
     assert e.value.code == "EBROKEN"
     o.create(9, (0, 3))  # recovery: a new world with another worker
+    # the boundary (a reading: "missed for 3 seconds" = the latest report is OLDER than the timeout):
+    # a report exactly 3 s old is not yet a miss, anything older is
+    o = WorldOracle(2)
+    o.create(1, (0, 1))
+    o.heartbeat(1, 10.0)
+    assert o.watchdog_check(13.0, 3.0) == [] and o.world_state(1) == ALIVE
+    assert o.watchdog_check(13.0 + 2 ** -20, 3.0) == [1] and o.world_state(1) == BROKEN
 
 
 def _schedule(seed, n_workers=8, n_events=300):
