@@ -39,7 +39,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kCopyWG = 1024;   // threads per workgroup, copy / broadcast
 constexpr int kCopyU = 4;       // 16-byte vectors in flight per thread
 constexpr int kReduceWG = 1024;  // threads per workgroup, all-reduce
-constexpr int kReduceU = 1;      // 16-byte vectors per rank in flight per thread, LDS-staged path
+// LDS-staged path: vectors per rank in the tile for a given chunk size (host and device agree on this)
+__host__ __device__ constexpr uint32_t lds_stride(uint32_t chunk_bytes) {
+  return (chunk_bytes + 15) / 16 < (uint32_t)kReduceWG ? (chunk_bytes + 15) / 16 : (uint32_t)kReduceWG;
+}
 // Register path: 16-byte vectors per rank in flight per thread, by number of ranks.  Two ranks give a
 // thread only two loads per vector; a second vector brings it to the four that the other counts have.
 constexpr int reduce_u(int n) { return n == 2 ? 2 : 1; }
@@ -439,39 +442,28 @@ __device__ __forceinline__ void reduce_vectors_any(const uint64_t* buf, uint64_t
 // LDS-staged path: the workgroup first lands one tile of every rank in LDS with wide loads,
 // then each thread sums its column across the staged rank tiles and writes all ranks.  The
 // staging decouples the (n x tile) read burst from the arithmetic and the write burst.
+// `stride` = vectors per rank in the tile (the chunk's vectors, at most one per thread); the launch sizes
+// the dynamic LDS to ranks x stride vectors, so small rank counts and small chunks leave room for a second
+// workgroup on the CU.
 template <bool BF16>
 __device__ __forceinline__ void reduce_vectors_lds(const rsrc_t* w, int nbuf, uint32_t wmask, uint32_t nvec,
-                                                   u32x4* tile) {
-  constexpr int U = kReduceU;
-  const uint32_t step = kReduceWG * U;
-  for (uint32_t base = 0; base < nvec; base += step) {
+                                                   u32x4* tile, uint32_t stride) {
+  for (uint32_t base = 0; base < nvec; base += stride) {
+    const uint32_t j = base + threadIdx.x;
+    const bool mine = threadIdx.x < stride && j < nvec;
 #pragma unroll
     for (int r = 0; r < kMaxBufs; ++r) {
-      if (r < nbuf) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          uint32_t j = base + threadIdx.x + u * kReduceWG;
-          if (j < nvec) tile[(r * U + u) * kReduceWG + threadIdx.x] = Io<u32x4>::ld(w[r], j * 16);
-        }
-      }
+      if (r < nbuf && mine) tile[r * stride + threadIdx.x] = Io<u32x4>::ld(w[r], j * 16);
     }
     __syncthreads();
-    u32x4 y[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
+    if (mine) {
       Acc<BF16> acc;
-      acc.init(tile[u * kReduceWG + threadIdx.x]);
-      for (int r = 1; r < nbuf; ++r) acc.add(tile[(r * U + u) * kReduceWG + threadIdx.x]);
-      y[u] = acc.out();
-    }
+      acc.init(tile[threadIdx.x]);
+      for (int r = 1; r < nbuf; ++r) acc.add(tile[r * stride + threadIdx.x]);
+      const u32x4 y = acc.out();
 #pragma unroll
-    for (int r = 0; r < kMaxBufs; ++r) {
-      if (r < nbuf && ((wmask >> r) & 1u)) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          uint32_t j = base + threadIdx.x + u * kReduceWG;
-          if (j < nvec) Io<u32x4>::st(w[r], j * 16, y[u]);
-        }
+      for (int r = 0; r < kMaxBufs; ++r) {
+        if (r < nbuf && ((wmask >> r) & 1u)) Io<u32x4>::st(w[r], j * 16, y);
       }
     }
     __syncthreads();
@@ -506,7 +498,7 @@ __device__ __forceinline__ void reduce_scalar(const rsrc_t* w, int nbuf, uint32_
 template <bool LDS>
 __global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs a, RingSlot* __restrict__ slots,
                                                           uint32_t* __restrict__ host_flags) {
-  __shared__ u32x4 tile[LDS ? kMaxBufs * kReduceU * kReduceWG : 1];
+  extern __shared__ u32x4 tile[];  // LDS-staged variant: ranks x stride vectors, sized by the launch
   const uint32_t c = blockIdx.x;
   const int op = find_op(a.first_chunk, (int)a.n, c);
   const uint64_t nbytes = a.e[op].nbytes;
@@ -546,8 +538,9 @@ __global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs a, RingS
   if ((align & 15) == 0) {
     nvec = (uint32_t)len >> 4;
     if (LDS) {
-      if (bf16) reduce_vectors_lds<true>(w, (int)nbuf, wmask, nvec, tile);
-      else reduce_vectors_lds<false>(w, (int)nbuf, wmask, nvec, tile);
+      const uint32_t stride = lds_stride((uint32_t)chunk);
+      if (bf16) reduce_vectors_lds<true>(w, (int)nbuf, wmask, nvec, tile, stride);
+      else reduce_vectors_lds<false>(w, (int)nbuf, wmask, nvec, tile, stride);
     } else {
       if (bf16) reduce_vectors_any<true>(buf, off, (uint32_t)len, (int)nbuf, wmask, nvec);
       else reduce_vectors_any<false>(buf, off, (uint32_t)len, (int)nbuf, wmask, nvec);
@@ -755,6 +748,10 @@ class HipDevice : public Device {
     dep_events_.assign(kDepEvents, nullptr);
     for (auto& e : dep_events_)
       if (chk(hipEventCreateWithFlags(&e, hipEventDisableTiming))) return MW_EHIP;
+    // the LDS-staged reduce kernel takes up to 8 ranks x 16 KiB of dynamic LDS, above the 64 KiB default limit
+    if (chk(hipFuncSetAttribute(reinterpret_cast<const void*>(&mw_k_reduce<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxBufs * kReduceWG * 16)))
+      return MW_EHIP;
     if (chk(hipDeviceSynchronize())) return MW_EHIP;
     ready_ = true;
     return MW_OK;
@@ -984,7 +981,9 @@ class HipDevice : public Device {
       if (kind == kBcast) {
         hipLaunchKernelGGL(mw_k_bcast, dim3(at), dim3(kCopyWG), 0, data_[kind], a, slots_, flags_dev_);
       } else if (cfg_.reduce_lds) {
-        hipLaunchKernelGGL(mw_k_reduce<true>, dim3(at), dim3(kReduceWG), 0, data_[kind], a, slots_, flags_dev_);
+        uint32_t lds = 0;
+        for (int i = 0; i < n; ++i) lds = std::max(lds, a.e[i].nbuf * lds_stride(a.e[i].chunk_bytes) * 16u);
+        hipLaunchKernelGGL(mw_k_reduce<true>, dim3(at), dim3(kReduceWG), lds, data_[kind], a, slots_, flags_dev_);
       } else {
         hipLaunchKernelGGL(mw_k_reduce<false>, dim3(at), dim3(kReduceWG), 0, data_[kind], a, slots_, flags_dev_);
       }
