@@ -21,7 +21,7 @@ ITEMSIZE = {"f32": 4, "bf16": 2}
 
 
 @dataclass
-class GpuRun:
+class DeviceRun:
     status: dict = field(default_factory=dict)      # posting op index -> "done" / "pending" / "broken" / "mismatch"
     snapshots: dict = field(default_factory=dict)   # check op index -> np.uint8 array
     world_state: dict = field(default_factory=dict)
@@ -84,7 +84,7 @@ def wait_all(outstanding, status, timeout_s=120.0):
 
 
 def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn=None):
-    """Execute `trace`; returns a GpuRun.  mw_init / mw_shutdown bracket the run.
+    """Execute `trace`; returns a DeviceRun.  mw_init / mw_shutdown bracket the run.
 
     check_fn(idx, op, bufs), if given, is called at every "check" op with the dict of live device
     tensors (buffer id -> uint8 tensor) once everything outstanding has completed; use it with
@@ -94,7 +94,7 @@ def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn
     pools = DevicePools(host_pools, dev)
     streams = [torch.cuda.Stream(device=dev) for _ in range(trace.n_streams)]
     cur = torch.cuda.current_stream(dev)
-    out = GpuRun()
+    out = DeviceRun()
     bufs = {}
     outstanding = []
     touched = False  # buffers were (re)initialised on torch's stream since the last ordering point
