@@ -168,3 +168,84 @@ def test_headline_workload_in_the_benchmarks_own_loop(gpu, host_pools):
             torch.cuda.synchronize()
     finally:
         mw.mw_shutdown()
+
+
+def test_every_operation_at_the_large_payload_of_the_collectives_benchmark():
+    """One world of 4 ranks, 64 MiB fp32 per rank (the payload `bench.py --workload collectives` times), all
+    seven operations, every byte of every result against the oracle's per-operation functions."""
+    import time
+
+    import torch
+
+    from paper_2407_08980_amd import binding as mw
+
+    n, S = 4, 64 << 20
+    count = S // 4
+    mw.mw_init(0, n)
+    try:
+        mw.mw_world_create(0, list(range(n)))
+
+        def wait(hs):
+            mw.mw_flush()
+            ps = mw.PollSet(hs)
+            t0 = time.time()
+            while ps.poll():
+                assert time.time() - t0 < 60
+            assert list(ps.states) == [mw.MW_DONE] * len(hs)
+
+        rng = np.random.default_rng(64)
+        host = [rng.integers(-6, 7, size=count).astype(np.float32).view(np.uint8) for _ in range(n)]  # exact sums
+        small = [torch.from_numpy(h).cuda() for h in host]
+        big = [torch.full((n * S,), 0xA5, dtype=torch.uint8, device="cuda") for _ in range(n)]
+        NONE = mw.STREAM_NONE
+
+        # send / recv: 0 -> 1 into a fresh buffer
+        dst = torch.zeros(S, dtype=torch.uint8, device="cuda")
+        wait([mw.mw_send(0, 0, 1, small[0].data_ptr(), count, mw.MW_F32, NONE),
+              mw.mw_recv(0, 0, 1, dst.data_ptr(), count, mw.MW_F32, NONE)])
+        assert np.array_equal(dst.cpu().numpy(), oracle.copy_result(host[0]))
+        # all-gather
+        wait([mw.mw_all_gather(0, r, small[r].data_ptr(), big[r].data_ptr(), count, mw.MW_F32, NONE) for r in range(n)])
+        want = oracle.all_gather_result(host)
+        for r in range(n):
+            assert np.array_equal(big[r].cpu().numpy(), want), r
+        # gather to rank 2 (the other ranks' big buffers must stay as they are)
+        for b in big:
+            b.fill_(0x5A)
+        wait([mw.mw_gather(0, r, 2, small[r].data_ptr(), big[r].data_ptr() if r == 2 else None, count, mw.MW_F32, NONE)
+              for r in range(n)])
+        assert np.array_equal(big[2].cpu().numpy(), oracle.gather_result(host))
+        assert all(bool((big[r] == 0x5A).all()) for r in range(n) if r != 2)
+        # scatter from rank 1: its big buffer holds the gathered tensor of before
+        big[1].copy_(big[2])
+        outs = [torch.zeros(S, dtype=torch.uint8, device="cuda") for _ in range(n)]
+        wait([mw.mw_scatter(0, r, 1, big[1].data_ptr() if r == 1 else None, outs[r].data_ptr(), count, mw.MW_F32, NONE)
+              for r in range(n)])
+        src = oracle.gather_result(host)
+        for r in range(n):
+            assert np.array_equal(outs[r].cpu().numpy(), oracle.scatter_result(src, n, r)), r
+        # broadcast from rank 3 into the scatter outputs
+        outs[3].copy_(small[3])
+        wait([mw.mw_broadcast(0, r, 3, outs[r].data_ptr(), count, mw.MW_F32, NONE) for r in range(n)])
+        want = oracle.broadcast_result([o.cpu().numpy() if r == 3 else None for r, o in enumerate(outs)], 3)
+        for r in range(n):
+            assert np.array_equal(outs[r].cpu().numpy(), want[r]), r
+        # reduce to rank 1, then all-reduce (integer-valued inputs: the float64 sum is exactly representable)
+        work = [s.clone() for s in small]
+        wait([mw.mw_reduce_sum(0, r, 1, work[r].data_ptr(), count, mw.MW_F32, NONE) for r in range(n)])
+        s, sabs = oracle.reduce_result_f64(host, count, oracle.F32)
+        got = work[1].cpu().numpy()
+        assert oracle.allreduce_within_tolerance(got, s, sabs, count, oracle.F32)[0]
+        assert np.array_equal(got.view(np.float32).astype(np.float64), s)
+        for r in (0, 2, 3):
+            assert np.array_equal(work[r].cpu().numpy(), host[r]), r
+        work = [s_.clone() for s_ in small]
+        wait([mw.mw_allreduce_sum(0, r, work[r].data_ptr(), count, mw.MW_F32, NONE) for r in range(n)])
+        s, sabs = oracle.allreduce_sum_f64(host, count, oracle.F32)
+        ordered = oracle.allreduce_sum_ordered(host, count, oracle.F32)
+        for r in range(n):
+            got = work[r].cpu().numpy()
+            assert oracle.allreduce_within_tolerance(got, s, sabs, count, oracle.F32)[0], r
+            assert np.array_equal(got, ordered), r
+    finally:
+        mw.mw_shutdown()
