@@ -7,6 +7,16 @@ import numpy as np
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
+def hostcheck_library():
+    """The host runtime linked with the byte-less device double, loaded.  tests/test_host_mutants.py points
+    MW_HOSTCHECK_UNDER_TEST at a deliberately broken build to see that these tests notice."""
+    import ctypes
+
+    from paper_2407_08980_amd import build as mwbuild
+
+    return ctypes.CDLL(os.environ.get("MW_HOSTCHECK_UNDER_TEST") or mwbuild.fresh_hostcheck())
+
+
 def golden(name):
     return os.path.join(ROOT, "tests", "golden", name)
 

@@ -15,12 +15,12 @@ import pytest
 from paper_2407_08980_amd import binding as mw
 from paper_2407_08980_amd import build as mwbuild
 
-from helpers import ROOT
+from helpers import ROOT, hostcheck_library
 
 
 @pytest.fixture(scope="module")
 def hostlib():
-    lib = C.CDLL(mwbuild.fresh_hostcheck())
+    lib = hostcheck_library()
     lib.mwt_log_entry.argtypes = [C.c_int, C.POINTER(C.c_uint64)]
     old = mw._lib
     mw.use_library(lib)

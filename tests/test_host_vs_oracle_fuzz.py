@@ -14,12 +14,14 @@ from oracle.mw_oracle import OracleError
 from paper_2407_08980_amd import binding as mw
 from paper_2407_08980_amd import build as mwbuild
 
+from helpers import hostcheck_library
+
 STATE = {mw.MW_DONE: DONE, mw.MW_PENDING: PENDING, mw.MW_BROKEN: BROKEN, mw.MW_EMISMATCH: MISMATCH}
 
 
 @pytest.fixture(scope="module")
 def hostlib():
-    lib = C.CDLL(mwbuild.fresh_hostcheck())
+    lib = hostcheck_library()
     old = mw._lib
     mw.use_library(lib)
     yield lib

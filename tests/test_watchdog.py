@@ -19,10 +19,12 @@ from oracle.mw_oracle import OracleError
 from paper_2407_08980_amd import binding as mw
 from paper_2407_08980_amd import build as mwbuild
 
+from helpers import hostcheck_library
+
 
 @pytest.fixture(scope="module")
 def hostlib():
-    lib = C.CDLL(mwbuild.fresh_hostcheck())
+    lib = hostcheck_library()
     old = mw._lib
     mw.use_library(lib)
     yield lib
@@ -145,6 +147,12 @@ def test_runtime_matches_oracle_with_explicit_clock(hostlib, seed):
         with pytest.raises(mw.MwError) as e:
             mw.mw_world_create(99, [dead, (dead + 1) % 8])
         assert e.value.code == mw.MW_EBROKEN
+        alive = next(k for k in range(8) if k not in o.dead)  # the boundary: exactly as old as the timeout is no miss
+        mw.mw_heartbeat_at(alive, 1000.0)
+        mw.mw_watchdog_check_at(1000.0 + timeout, timeout)
+        assert mw.mw_worker_state(alive) == mw.MW_ALIVE
+        mw.mw_watchdog_check_at(1000.0 + timeout + 2 ** -20, timeout)
+        assert mw.mw_worker_state(alive) == mw.MW_BROKEN
     finally:
         mw.mw_shutdown()
 
