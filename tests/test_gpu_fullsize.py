@@ -185,7 +185,9 @@ def test_every_operation_at_the_large_payload_of_the_collectives_benchmark():
     try:
         mw.mw_world_create(0, list(range(n)))
 
-        def wait(hs):
+        def wait(post):
+            torch.cuda.synchronize()  # the posts below state (MW_STREAM_NONE) that their buffers are final
+            hs = post()
             mw.mw_flush()
             ps = mw.PollSet(hs)
             t0 = time.time()
@@ -201,38 +203,38 @@ def test_every_operation_at_the_large_payload_of_the_collectives_benchmark():
 
         # send / recv: 0 -> 1 into a fresh buffer
         dst = torch.zeros(S, dtype=torch.uint8, device="cuda")
-        wait([mw.mw_send(0, 0, 1, small[0].data_ptr(), count, mw.MW_F32, NONE),
+        wait(lambda: [mw.mw_send(0, 0, 1, small[0].data_ptr(), count, mw.MW_F32, NONE),
               mw.mw_recv(0, 0, 1, dst.data_ptr(), count, mw.MW_F32, NONE)])
         assert np.array_equal(dst.cpu().numpy(), oracle.copy_result(host[0]))
         # all-gather
-        wait([mw.mw_all_gather(0, r, small[r].data_ptr(), big[r].data_ptr(), count, mw.MW_F32, NONE) for r in range(n)])
+        wait(lambda: [mw.mw_all_gather(0, r, small[r].data_ptr(), big[r].data_ptr(), count, mw.MW_F32, NONE) for r in range(n)])
         want = oracle.all_gather_result(host)
         for r in range(n):
             assert np.array_equal(big[r].cpu().numpy(), want), r
         # gather to rank 2 (the other ranks' big buffers must stay as they are)
         for b in big:
             b.fill_(0x5A)
-        wait([mw.mw_gather(0, r, 2, small[r].data_ptr(), big[r].data_ptr() if r == 2 else None, count, mw.MW_F32, NONE)
+        wait(lambda: [mw.mw_gather(0, r, 2, small[r].data_ptr(), big[r].data_ptr() if r == 2 else None, count, mw.MW_F32, NONE)
               for r in range(n)])
         assert np.array_equal(big[2].cpu().numpy(), oracle.gather_result(host))
         assert all(bool((big[r] == 0x5A).all()) for r in range(n) if r != 2)
         # scatter from rank 1: its big buffer holds the gathered tensor of before
         big[1].copy_(big[2])
         outs = [torch.zeros(S, dtype=torch.uint8, device="cuda") for _ in range(n)]
-        wait([mw.mw_scatter(0, r, 1, big[1].data_ptr() if r == 1 else None, outs[r].data_ptr(), count, mw.MW_F32, NONE)
+        wait(lambda: [mw.mw_scatter(0, r, 1, big[1].data_ptr() if r == 1 else None, outs[r].data_ptr(), count, mw.MW_F32, NONE)
               for r in range(n)])
         src = oracle.gather_result(host)
         for r in range(n):
             assert np.array_equal(outs[r].cpu().numpy(), oracle.scatter_result(src, n, r)), r
         # broadcast from rank 3 into the scatter outputs
         outs[3].copy_(small[3])
-        wait([mw.mw_broadcast(0, r, 3, outs[r].data_ptr(), count, mw.MW_F32, NONE) for r in range(n)])
+        wait(lambda: [mw.mw_broadcast(0, r, 3, outs[r].data_ptr(), count, mw.MW_F32, NONE) for r in range(n)])
         want = oracle.broadcast_result([o.cpu().numpy() if r == 3 else None for r, o in enumerate(outs)], 3)
         for r in range(n):
             assert np.array_equal(outs[r].cpu().numpy(), want[r]), r
         # reduce to rank 1, then all-reduce (integer-valued inputs: the float64 sum is exactly representable)
         work = [s.clone() for s in small]
-        wait([mw.mw_reduce_sum(0, r, 1, work[r].data_ptr(), count, mw.MW_F32, NONE) for r in range(n)])
+        wait(lambda: [mw.mw_reduce_sum(0, r, 1, work[r].data_ptr(), count, mw.MW_F32, NONE) for r in range(n)])
         s, sabs = oracle.reduce_result_f64(host, count, oracle.F32)
         got = work[1].cpu().numpy()
         assert oracle.allreduce_within_tolerance(got, s, sabs, count, oracle.F32)[0]
@@ -240,7 +242,7 @@ def test_every_operation_at_the_large_payload_of_the_collectives_benchmark():
         for r in (0, 2, 3):
             assert np.array_equal(work[r].cpu().numpy(), host[r]), r
         work = [s_.clone() for s_ in small]
-        wait([mw.mw_allreduce_sum(0, r, work[r].data_ptr(), count, mw.MW_F32, NONE) for r in range(n)])
+        wait(lambda: [mw.mw_allreduce_sum(0, r, work[r].data_ptr(), count, mw.MW_F32, NONE) for r in range(n)])
         s, sabs = oracle.allreduce_sum_f64(host, count, oracle.F32)
         ordered = oracle.allreduce_sum_ordered(host, count, oracle.F32)
         for r in range(n):
