@@ -107,6 +107,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2407_08980_amd.build` "
                                "(there is no fallback path)")
+        try:  # one HIP runtime per process: when torch is there, its copy must be the one already loaded
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         _lib = declare(C.CDLL(LIB_PATH))
         check_build(_lib, LIB_PATH)
     return _lib
