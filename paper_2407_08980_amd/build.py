@@ -15,6 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmw.so")
 LIB_HOSTCHECK = os.path.join(HERE, "libmw_hostcheck.so")
+ABI_CHECK = os.path.join(HERE, "abi_check.bin")  # tests/abi_check.cpp: a program that uses the C ABI directly
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 HIP_FLAGS = [
@@ -85,9 +86,17 @@ def fresh_hostcheck():
     return LIB_HOSTCHECK
 
 
+def build_abi_check():
+    """The test program of the C ABI, linked against the product library beside it."""
+    src = os.path.join(os.path.dirname(HERE), "tests", "abi_check.cpp")
+    return _run([HIPCC, "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wno-unused-command-line-argument", src, "-o", ABI_CHECK,
+                 "-L" + HERE, "-lmw", "-Wl,-rpath,$ORIGIN"])
+
+
 def build_all():
     out = build_product()
     out += build_hostcheck()
+    out += build_abi_check()
     return out
 
 
