@@ -36,26 +36,25 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kCopyWG = 1024;   // threads per workgroup, copy / broadcast
-constexpr int kCopyU = 4;       // 16-byte vectors in flight per thread
-constexpr int kReduceWG = 1024;  // threads per workgroup, all-reduce
-// LDS-staged path: vectors per rank in the tile for a given chunk size (host and device agree on this)
+constexpr int kCopyWG = 1024;    // threads per workgroup, copy / broadcast
+constexpr int kCopyU = 4;        // 16-byte vectors in flight per thread
+constexpr int kReduceWG = 1024;  // threads per workgroup, (all-)reduce
+constexpr int kCopyMax = 72;     // entries per copy launch (kernel arguments stay under 4 KiB)
+constexpr int kCollMax = 36;     // entries per fan-out / reduce launch
+// (All-)reduce, register path: 16-byte vectors per rank in flight per thread, by number of ranks.  Two ranks
+// give a thread only two loads per vector; a second vector brings it to the four that the other counts have.
+constexpr int reduce_u(int n) { return n == 2 ? 2 : 1; }
+// (All-)reduce, LDS-staged path: vectors per rank in the tile for a given chunk size (host and device agree)
 __host__ __device__ constexpr uint32_t lds_stride(uint32_t chunk_bytes) {
   return (chunk_bytes + 15) / 16 < (uint32_t)kReduceWG ? (chunk_bytes + 15) / 16 : (uint32_t)kReduceWG;
 }
-// Register path: 16-byte vectors per rank in flight per thread, by number of ranks.  Two ranks give a
-// thread only two loads per vector; a second vector brings it to the four that the other counts have.
-constexpr int reduce_u(int n) { return n == 2 ? 2 : 1; }
-constexpr int kCopyMax = 72;    // entries per copy launch (kernel arguments stay under 4 KiB)
-constexpr int kCollMax = 36;    // entries per fan-out / reduce launch
 
 // An operation is one or more *entries* of one kernel: a copy is one copy entry, a gather or a
 // scatter n copy entries, a broadcast one fan-out entry, an all-gather n (or more) fan-out entries,
 // an (all-)reduce one reduce entry.  All entries of an operation share its ring slot; `op_chunks`
 // is the chunk count of the whole operation, which is what the arrival counter runs up to.
 // flags: bit 0 = this entry journals the descriptor; bits 1-7 = element type; bits 8-15 = OpKind;
-// bits 16-23 = ranks;
-// bits 24-31 = mask of the ranks whose buffer a reduce entry stores to.
+// bits 16-23 = ranks of the operation; bits 24-31 = mask of the ranks whose buffer a reduce entry stores to.
 struct CopyEnt {
   uint64_t src, dst, nbytes;
   uint32_t slot, gen;
@@ -263,7 +262,7 @@ __global__ __launch_bounds__(kCopyWG) void mw_k_copy(const CopyArgs a, RingSlot*
     d->buf[1] = dst;
     d->nbytes = nbytes;
     d->kind = (flags >> 8) & 0xFFu;
-    d->dtype = 0;
+    d->dtype = (flags >> 1) & 0x7Fu;
     d->nbuf = (flags >> 16) & 0xFFu;
     d->world_id = a.e[op].world_id;
     d->world_epoch = a.e[op].world_epoch;

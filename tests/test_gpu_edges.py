@@ -322,7 +322,7 @@ def test_ring_journal_header_and_isolation_across_abort(torch, mw):
     assert len(used) == 1
     s = used[0]
     assert s["bufs"][:2] == (bufs[40][0].data_ptr(), bufs[40][1].data_ptr()) and s["nbytes"] == n
-    assert (s["kind"], s["nbuf"], s["world"], s["epoch"]) == (0, 2, 40, 0)
+    assert (s["kind"], s["nbuf"], s["world"], s["epoch"], s["dtype"]) == (0, 2, 40, 0, mw.MW_BF16)
     assert s["nchunks"] * s["chunk"] >= n > (s["nchunks"] - 1) * s["chunk"]
     assert s["arrived"] == 0 and s["done_gen"] == s["gen"]  # counter re-armed, completion published
     r42 = mw.mw_debug_ring_read(42)
