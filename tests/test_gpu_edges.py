@@ -223,6 +223,30 @@ def test_many_operations_in_one_flush(torch, mw):
         assert np.array_equal(xdev[i][0][1].cpu().numpy(), want)
 
 
+def test_more_outstanding_operations_than_ring_slots(torch, mw):
+    """One world's ring has 128 slots; 300 messages are posted before the first poll.  The ones that find no slot
+    wait on the host until earlier ones retire; all of them arrive, in order, byte for byte."""
+    mw.mw_world_create(0, [0, 1])
+    n, size = 300, 2048
+    src = np.stack([rand_bytes(size, 5000 + k) for k in range(n)])
+    src[:, 0] = np.arange(n) % 251  # a stamp: the k-th receive must hold the k-th send
+    sdev = torch.from_numpy(src).cuda()
+    ddev = torch.full((n, size), 0xA5, dtype=torch.uint8, device="cuda")
+    hs = []
+    for k in range(n):  # all sends first, then all receives: matching is FIFO per (world, src, dst)
+        hs.append(mw.mw_send(0, 0, 1, sdev[k].data_ptr(), size // 4, mw.MW_F32))
+    for k in range(n):
+        hs.append(mw.mw_recv(0, 0, 1, ddev[k].data_ptr(), size // 4, mw.MW_F32))
+    assert mw.mw_pending_ops() == n
+    mw.mw_flush()
+    assert mw.mw_pending_ops() == n  # 128 in flight, the rest queued: nothing is complete before a poll sees it
+    assert wait(mw, hs) == [mw.MW_DONE] * len(hs)
+    got = ddev.cpu().numpy()
+    for k in range(n):
+        assert np.array_equal(got[k], oracle.copy_result(src[k])), k
+    assert mw.mw_pending_ops() == 0
+
+
 def test_early_completion_is_visible(torch, mw):
     """A small message batched with large ones is reported complete while the launch is still
     running; its bytes must be readable (here: by a DMA copy to the host) at that moment."""
