@@ -162,7 +162,7 @@ int mw_poll(mw_handle h);
 
 /* Failures of workers that share a host are silent (Sec. 3.2 "Reliable fault detection"), so each
  * worker reports its health periodically and a watchdog declares a worker failed when its reports
- * have been missing for longer than a timeout ("e.g., 3 seconds"); the worlds containing it are then
+ * have been missing for longer than a timeout (the paper's example is 3 seconds); the worlds containing it are then
  * aborted exactly as by mw_worker_abort, and no others.
  *
  * mw_heartbeat(worker): the worker is alive now (steady clock).  A worker is watched from its first

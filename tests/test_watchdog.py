@@ -59,7 +59,7 @@ def test_oracle_watchdog_paper_numbers():
         o.create(9, (0, 2))
     assert e.value.code == "EBROKEN"
     o.create(9, (0, 3))  # recovery: a new world with another worker
-    # the boundary (a reading: "missed for 3 seconds" = the latest report is OLDER than the timeout):
+    # the boundary (a reading: reports count as missing once the latest one is OLDER than the timeout):
     # a report exactly 3 s old is not yet a miss, anything older is
     o = WorldOracle(2)
     o.create(1, (0, 1))
