@@ -91,7 +91,7 @@ def run_trace(trace, materialize, data_bufs=None):
         elif k == "free":
             live.pop(op.buf, None)
             last_post.pop(op.buf, None)
-        elif k == "wait":
+        elif k in ("wait", "flush"):
             pass
         else:
             raise OracleError("EINVAL", f"unknown trace op {k}")

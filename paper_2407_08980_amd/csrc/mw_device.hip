@@ -185,6 +185,9 @@ __device__ __forceinline__ void retire_chunk(RingSlot* slots, uint32_t* host_fla
     if (prev + 1 == nchunks) {
       __hip_atomic_store(&s->arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(&s->done_gen, gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // The host may recycle the slot as soon as it sees the flag: the re-arm and the generation must
+      // have been performed before the flag store is issued.  One thread per operation: costs nothing.
+      __builtin_amdgcn_s_waitcnt(0);
       __hip_atomic_store(&host_flags[slot], gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
   }
@@ -577,9 +580,7 @@ class HipDevice : public Device {
   void shutdown() override {
     if (!ready_) return;
     (void)hipSetDevice(dev_);
-    for (auto& kind : lanes_)
-      for (auto& st : kind) (void)hipStreamSynchronize(st);
-    (void)hipStreamSynchronize(ctl_);
+    (void)hipDeviceSynchronize();  // operations behind a busy caller stream run on that stream
     release();
   }
 
@@ -588,64 +589,70 @@ class HipDevice : public Device {
     cfg_.reduce_lds = cfg.reduce_lds;
   }
 
-  int launch(const LaunchOp* ops, int n, void* const* streams, int n_streams, uint8_t* launched) override {
+  int launch(const LaunchOp* ops, const OpDeps* deps, int n, uint8_t* launched) override {
     launched_ = launched;
+    cur_slots_ = slots_;
+    cur_flags_ = flags_dev_;
+    host_flags_ok_ = true;
     if (chk(hipSetDevice(dev_))) return MW_EHIP;
-    // Each kernel kind has its own stream so that a copy, a broadcast and an all-reduce launch of one
-    // flush overlap.  Order every stream used by this flush after the callers' busy streams.
-    bool used[kNumKinds] = {};
-    for (int i = 0; i < n; ++i) used[kernel_of(ops[i].kind)] = true;
-    uint64_t bytes[kNumKinds] = {};
-    for (int i = 0; i < n; ++i) {  // traffic: every buffer once, (all-)reduce reads and writes them
-      const uint32_t k = kernel_of(ops[i].kind);
-      bytes[k] += ops[i].nbytes * ops[i].nbuf * (k == kReduce ? 2 : 1);
-    }
-    for (uint32_t k = 0; k < kNumKinds; ++k) {
-      if (!used[k]) continue;
-      // a kernel of >~10 us: 64 MiB of copy traffic, 32 MiB of reduce traffic (its small-chunk launches run slower)
-      const uint64_t medium = k == kReduce ? (32ull << 20) : (64ull << 20);
-      if (bytes[k] >= kLargeLaunchBytes) data_[k] = lanes_[k][0];
-      else if (bytes[k] >= medium) data_[k] = lanes_[k][1 + lane_cursor_[k]++ % (kLanes - 1)];
-      else data_[k] = lanes_[k][1];
-    }
-    for (int i = 0; i < n_streams; ++i) {
-      // A stream with nothing pending imposes no ordering: skip the event and the barrier packet.
-      hipError_t q = hipStreamQuery(reinterpret_cast<hipStream_t>(streams[i]));
-      if (q == hipSuccess) continue;
-      if (q != hipErrorNotReady) {
-        chk(q);
-        return MW_EHIP;
-      }
-      hipEvent_t ev = dep_events_[dep_cursor_];
-      dep_cursor_ = (dep_cursor_ + 1) % kDepEvents;
-      if (chk(hipEventRecord(ev, reinterpret_cast<hipStream_t>(streams[i])))) return MW_EHIP;
-      for (uint32_t k = 0; k < kNumKinds; ++k)
-        if (used[k] && chk(hipStreamWaitEvent(data_[k], ev, 0))) return MW_EHIP;
-    }
-    // Expand every operation into the entries of its kernel and launch them kind by kind.  All
-    // entries of an operation stay in one launch (they share one chunk size and one arrival count).
-    int rc = MW_OK;
-    for (uint32_t kind = 0; kind < kNumKinds && rc == MW_OK; ++kind) {
-      if (!used[kind]) continue;
-      const size_t cap = kind == kCopy ? kCopyMax : kCollMax;
-      ents_.clear();
-      for (int i = 0; i < n && rc == MW_OK; ++i) {
-        if (kernel_of(ops[i].kind) != kind) continue;
-        const size_t before = ents_.size();
-        expand(ops[i], (uint32_t)i);
-        if (ents_.size() == before) {  // every segment already in place: nothing to move, complete now
-          __atomic_store_n(&flags_host_[ops[i].slot], ops[i].gen, __ATOMIC_RELEASE);
-          launched[i] = 1;
-          continue;
+    // Which caller streams still have work pending?  One query per distinct stream.  A stream with nothing
+    // pending imposes no ordering: no event, no barrier packet.
+    dep_streams_.clear();
+    dep_busy_.clear();
+    group_of_.assign((size_t)n, -1);
+    bool any_dependent = false;
+    for (int i = 0; i < n; ++i) {
+      for (int k = 0; k < deps[i].n; ++k) {
+        void* st = deps[i].stream[k];
+        size_t j = 0;
+        while (j < dep_streams_.size() && dep_streams_[j] != st) ++j;
+        if (j == dep_streams_.size()) {
+          hipError_t q = hipStreamQuery(reinterpret_cast<hipStream_t>(st));
+          if (q != hipSuccess && q != hipErrorNotReady) {
+            chk(q);
+            return MW_EHIP;
+          }
+          dep_streams_.push_back(st);
+          dep_busy_.push_back(q == hipErrorNotReady);
         }
-        if (ents_.size() > cap) {  // launch what was gathered before this operation, keep its entries
-          one_.assign(ents_.begin() + (long)before, ents_.end());
-          ents_.resize(before);
-          rc = launch_entries(kind);
-          ents_.swap(one_);
+        if (dep_busy_[j] && group_of_[(size_t)i] < 0) group_of_[(size_t)i] = (int)j;  // its first busy stream
+      }
+      any_dependent |= group_of_[(size_t)i] >= 0;
+    }
+    // Operations whose buffers are final go to the library's own lanes and wait for nothing.
+    int rc = launch_group(ops, n, -1);
+    if (rc != MW_OK || !any_dependent) return rc;
+    // An operation behind a busy caller stream is enqueued ON that stream (behind its other busy streams
+    // too, through events), so it is ordered by the stream itself and never stands in a lane in front of
+    // operations of other worlds: a producer that is slow, or stuck, holds up only the operations that named
+    // its stream (Sec. 3.2: a pending operation in one world must not hold up another).
+    for (size_t g = 0; g < dep_streams_.size() && rc == MW_OK; ++g) {
+      if (!dep_busy_[g]) continue;
+      bool mine = false;
+      for (int i = 0; i < n; ++i) mine |= group_of_[(size_t)i] == (int)g;
+      if (!mine) continue;
+      hipStream_t target = reinterpret_cast<hipStream_t>(dep_streams_[g]);
+      waited_.clear();
+      for (int i = 0; i < n; ++i) {
+        if (group_of_[(size_t)i] != (int)g) continue;
+        for (int k = 0; k < deps[i].n; ++k) {
+          void* st = deps[i].stream[k];
+          if (st == dep_streams_[g]) continue;
+          size_t j = 0;
+          while (dep_streams_[j] != st) ++j;
+          if (!dep_busy_[j]) continue;
+          bool seen = false;
+          for (void* t : waited_) seen |= t == st;
+          if (seen) continue;
+          waited_.push_back(st);
+          hipEvent_t ev = dep_events_[dep_cursor_];
+          dep_cursor_ = (dep_cursor_ + 1) % kDepEvents;
+          if (chk(hipEventRecord(ev, reinterpret_cast<hipStream_t>(st)))) return MW_EHIP;
+          if (chk(hipStreamWaitEvent(target, ev, 0))) return MW_EHIP;
         }
       }
-      if (rc == MW_OK && !ents_.empty()) rc = launch_entries(kind);
+      for (uint32_t k = 0; k < kNumKinds; ++k) data_[k] = target;
+      rc = launch_group(ops, n, (int)g);
     }
     return rc;
   }
@@ -670,10 +677,7 @@ class HipDevice : public Device {
 
   int sync() override {
     if (chk(hipSetDevice(dev_))) return MW_EHIP;
-    for (auto& kind : lanes_)
-      for (auto& st : kind)
-        if (chk(hipStreamSynchronize(st))) return MW_EHIP;
-    if (chk(hipStreamSynchronize(ctl_))) return MW_EHIP;
+    if (chk(hipDeviceSynchronize())) return MW_EHIP;  // the lanes, and the caller streams operations were put on
     return MW_OK;
   }
 
@@ -751,6 +755,13 @@ class HipDevice : public Device {
     if (chk(hipFuncSetAttribute(reinterpret_cast<const void*>(&mw_k_reduce<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kMaxBufs * kReduceWG * 16)))
       return MW_EHIP;
+    // Host tables sized once, so that launching never grows them.
+    ents_.reserve(512);
+    one_.reserve(64);
+    chunks_.reserve(512);
+    op_chunks_.reserve(512);
+    chunk_bytes_.reserve(512);
+    group_of_.reserve(4096);
     if (chk(hipDeviceSynchronize())) return MW_EHIP;
     ready_ = true;
     return MW_OK;
@@ -909,6 +920,60 @@ class HipDevice : public Device {
     }
   }
 
+  // The operations of the dependency-free group (-1), on the library's lanes.
+  int launch_group(const LaunchOp* ops, int n, int group) {
+    if (group < 0) {
+      // Each kernel kind has its own streams so that a copy, a broadcast and an all-reduce launch of one
+      // flush overlap.
+      uint64_t bytes[kNumKinds] = {};
+      for (int i = 0; i < n; ++i) {  // traffic: every buffer once, (all-)reduce reads and writes them
+        if (group_of_[(size_t)i] >= 0) continue;
+        const uint32_t k = kernel_of(ops[i].kind);
+        bytes[k] += ops[i].nbytes * ops[i].nbuf * (k == kReduce ? 2 : 1);
+      }
+      for (uint32_t k = 0; k < kNumKinds; ++k) {
+        if (!bytes[k]) {
+          data_[k] = lanes_[k][1];
+          continue;
+        }
+        // a kernel of >~10 us: 64 MiB of copy traffic, 32 MiB of reduce traffic (its small-chunk launches run slower)
+        const uint64_t medium = k == kReduce ? (32ull << 20) : (64ull << 20);
+        if (bytes[k] >= kLargeLaunchBytes) data_[k] = lanes_[k][0];
+        else if (bytes[k] >= medium) data_[k] = lanes_[k][1 + lane_cursor_[k]++ % (kLanes - 1)];
+        else data_[k] = lanes_[k][1];
+      }
+    }
+    return run_group(ops, n, group);
+  }
+
+  // Expand every operation of `group` into the entries of its kernel and launch them kind by kind on
+  // data_[kind].  All entries of an operation stay in one launch (they share one arrival count).
+  int run_group(const LaunchOp* ops, int n, int group) {
+    int rc = MW_OK;
+    for (uint32_t kind = 0; kind < kNumKinds && rc == MW_OK; ++kind) {
+      const size_t cap = kind == kCopy ? kCopyMax : kCollMax;
+      ents_.clear();
+      for (int i = 0; i < n && rc == MW_OK; ++i) {
+        if (group_of_[(size_t)i] != group || kernel_of(ops[i].kind) != kind) continue;
+        const size_t before = ents_.size();
+        expand(ops[i], (uint32_t)i);
+        if (ents_.size() == before) {  // every segment already in place: nothing to move, complete now
+          if (host_flags_ok_) __atomic_store_n(&flags_host_[ops[i].slot], ops[i].gen, __ATOMIC_RELEASE);
+          launched_[i] = 1;
+          continue;
+        }
+        if (ents_.size() > cap) {  // launch what was gathered before this operation, keep its entries
+          one_.assign(ents_.begin() + (long)before, ents_.end());
+          ents_.resize(before);
+          rc = launch_entries(kind);
+          ents_.swap(one_);
+        }
+      }
+      if (rc == MW_OK && !ents_.empty()) rc = launch_entries(kind);
+    }
+    return rc;
+  }
+
   // Launch the gathered entries (ents_) as one kernel of `kind`.
   int launch_entries(uint32_t kind) {
     const int n = (int)ents_.size();
@@ -956,7 +1021,7 @@ class HipDevice : public Device {
                          op_chunks_[(size_t)i], e.flags};
       }
       a.first_chunk[n] = at;
-      hipLaunchKernelGGL(mw_k_copy, dim3(at), dim3(kCopyWG), 0, data_[kind], a, slots_, flags_dev_);
+      hipLaunchKernelGGL(mw_k_copy, dim3(at), dim3(kCopyWG), 0, data_[kind], a, cur_slots_, cur_flags_);
     } else {
       CollArgs& a = coll_args_;
       a.n = (uint32_t)n;
@@ -978,13 +1043,13 @@ class HipDevice : public Device {
       }
       a.first_chunk[n] = at;
       if (kind == kBcast) {
-        hipLaunchKernelGGL(mw_k_bcast, dim3(at), dim3(kCopyWG), 0, data_[kind], a, slots_, flags_dev_);
+        hipLaunchKernelGGL(mw_k_bcast, dim3(at), dim3(kCopyWG), 0, data_[kind], a, cur_slots_, cur_flags_);
       } else if (cfg_.reduce_lds) {
         uint32_t lds = 0;
         for (int i = 0; i < n; ++i) lds = std::max(lds, a.e[i].nbuf * lds_stride(a.e[i].chunk_bytes) * 16u);
-        hipLaunchKernelGGL(mw_k_reduce<true>, dim3(at), dim3(kReduceWG), lds, data_[kind], a, slots_, flags_dev_);
+        hipLaunchKernelGGL(mw_k_reduce<true>, dim3(at), dim3(kReduceWG), lds, data_[kind], a, cur_slots_, cur_flags_);
       } else {
-        hipLaunchKernelGGL(mw_k_reduce<false>, dim3(at), dim3(kReduceWG), 0, data_[kind], a, slots_, flags_dev_);
+        hipLaunchKernelGGL(mw_k_reduce<false>, dim3(at), dim3(kReduceWG), 0, data_[kind], a, cur_slots_, cur_flags_);
       }
     }
     if (chk(hipGetLastError())) return MW_EHIP;
@@ -1034,6 +1099,12 @@ class HipDevice : public Device {
   ProfAcc acc_[kNumKinds];
   std::vector<Ent> ents_, one_;
   uint8_t* launched_ = nullptr;  // the current launch() call's per-operation result array
+  RingSlot* cur_slots_ = nullptr;   // where the current launch's kernels count chunks in and publish completion:
+  uint32_t* cur_flags_ = nullptr;   // the arena and the host-pinned words
+  bool host_flags_ok_ = true;       // the current launch publishes to the host-pinned words
+  std::vector<void*> dep_streams_, waited_;  // distinct caller streams of the current launch() call
+  std::vector<uint8_t> dep_busy_;            // ... and whether each still had work pending
+  std::vector<int> group_of_;                // per operation: index of its first busy stream, or -1
   std::vector<uint32_t> chunks_, op_chunks_, chunk_bytes_;
   CopyArgs copy_args_{};
   CollArgs coll_args_{};

@@ -42,12 +42,20 @@ class NullDevice : public Device {
   }
   void shutdown() override { g_null = nullptr; }
   void set_config(const DeviceConfig&) override {}
-  int launch(const LaunchOp* ops, int n, void* const*, int n_streams, uint8_t* launched) override {
+  int launch(const LaunchOp* ops, const OpDeps* deps, int n, uint8_t* launched) override {
     std::lock_guard<std::mutex> g(st_.mu);
     if (st_.fail_next_launch) {
       st_.fail_next_launch = false;
       return MW_EHIP;
     }
+    std::vector<void*> distinct;
+    for (int i = 0; i < n; ++i)
+      for (int k = 0; k < deps[i].n; ++k) {
+        bool seen = false;
+        for (void* t : distinct) seen |= t == deps[i].stream[k];
+        if (!seen) distinct.push_back(deps[i].stream[k]);
+      }
+    const int n_streams = (int)distinct.size();
     int id = (int)st_.launch_sizes.size();
     st_.launch_sizes.push_back(n);
     st_.launch_streams.push_back(n_streams);

@@ -114,7 +114,7 @@ struct Context {
   std::vector<uint8_t> failed;       // the watchdog has declared the worker failed
 
   std::vector<LaunchOp> launch_buf;
-  std::vector<void*> stream_buf;
+  std::vector<OpDeps> deps_buf;
   std::vector<uint32_t> launched_buf;
   std::vector<uint8_t> launched_flags;
 };
@@ -222,7 +222,7 @@ void retire_one(Context& c, uint32_t opi) {
 int flush_locked(Context& c) {
   if (c.ready.empty()) return MW_OK;
   c.launch_buf.clear();
-  c.stream_buf.clear();
+  c.deps_buf.clear();
   c.launched_buf.clear();
   std::deque<uint32_t> deferred;
   while (!c.ready.empty()) {
@@ -245,18 +245,15 @@ int flush_locked(Context& c) {
     op.l.world_epoch = w.epoch;
     c.launch_buf.push_back(op.l);
     c.launched_buf.push_back(opi);
-    for (int i = 0; i < op.n_streams; ++i) {
-      void* s = op.streams[i];
-      bool seen = false;
-      for (void* t : c.stream_buf) seen |= (t == s);
-      if (!seen) c.stream_buf.push_back(s);
-    }
+    OpDeps d{};
+    d.n = op.n_streams;
+    for (int i = 0; i < op.n_streams; ++i) d.stream[i] = op.streams[i];
+    c.deps_buf.push_back(d);
   }
   c.ready.swap(deferred);
   if (c.launch_buf.empty()) return MW_OK;
   c.launched_flags.assign(c.launch_buf.size(), 0);
-  int rc = c.dev->launch(c.launch_buf.data(), (int)c.launch_buf.size(), c.stream_buf.data(),
-                         (int)c.stream_buf.size(), c.launched_flags.data());
+  int rc = c.dev->launch(c.launch_buf.data(), c.deps_buf.data(), (int)c.launch_buf.size(), c.launched_flags.data());
   // Operations the device took are in flight; on a failure the others go back to the queue, slots freed.
   for (size_t i = c.launched_buf.size(); i-- > 0;) {
     uint32_t opi = c.launched_buf[i];

@@ -94,6 +94,13 @@ struct LaunchOp {
   uint32_t world_epoch;
 };
 
+// The caller streams one operation is ordered after (hipStream_t as void*, NULL = the null stream;
+// MW_STREAM_NONE never appears here).  At most one per posted side.
+struct OpDeps {
+  void* stream[kMaxBufs];
+  int n;
+};
+
 struct DeviceConfig {
   uint32_t total_slots;   // ring slots in the arena
   uint32_t total_rings;   // ring headers in the arena
@@ -107,11 +114,12 @@ class Device {
   virtual int init(int hip_device, const DeviceConfig& cfg) = 0;
   virtual void shutdown() = 0;
   virtual void set_config(const DeviceConfig& cfg) = 0;
-  // Launch `n` operations (any mix of kinds, any worlds), ordered after the work already
-  // enqueued on each of `streams` (hipStream_t as void*, NULL = null stream).  Returns 0 or MW_EHIP;
-  // launched[i] is set to 1 for every operation that was enqueued on the device (all of them on
-  // success; on failure the others were not and may be retried).
-  virtual int launch(const LaunchOp* ops, int n, void* const* streams, int n_streams, uint8_t* launched) = 0;
+  // Launch `n` operations (any mix of kinds, any worlds); operation i is ordered after the work already
+  // enqueued on each stream of deps[i], and on nothing else: an operation never waits for a stream that
+  // only another operation named (Sec. 3.2: a pending operation in one world must not hold up another).
+  // Returns 0 or MW_EHIP; launched[i] is set to 1 for every operation that was enqueued on the device (all
+  // of them on success; on failure the others were not and may be retried).
+  virtual int launch(const LaunchOp* ops, const OpDeps* deps, int n, uint8_t* launched) = 0;
   // Write a ring header (world create / abort marker).  Asynchronous, on the library's stream.
   virtual int mark_world(uint32_t ring_index, const RingHeader& h) = 0;
   // Host-visible completion word of a slot (acquire load of the pinned mirror).

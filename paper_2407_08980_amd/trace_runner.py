@@ -83,12 +83,13 @@ def wait_all(outstanding, status, timeout_s=120.0):
             raise TimeoutError(f"{mw.mw_pending_ops()} operations did not complete within {timeout_s} s")
 
 
-def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn=None):
+def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn=None, on_init=None, on_exit=None):
     """Execute `trace`; returns a DeviceRun.  mw_init / mw_shutdown bracket the run.
 
     check_fn(idx, op, bufs), if given, is called at every "check" op with the dict of live device
     tensors (buffer id -> uint8 tensor) once everything outstanding has completed; use it with
-    snapshots=False to verify large buffers on the device instead of copying them out."""
+    snapshots=False to verify large buffers on the device instead of copying them out.
+    on_init() / on_exit() run right after mw_init and right before mw_shutdown (e.g. to run the watchdog)."""
     dev = torch.device("cuda", device)
     torch.cuda.set_device(dev)
     pools = DevicePools(host_pools, dev)
@@ -112,6 +113,8 @@ def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn
 
     mw.mw_init(device, trace.n_workers)
     try:
+        if on_init is not None:
+            on_init()
         t_start = time.time()
         for idx, op in enumerate(trace.ops):
             k = op.kind
@@ -156,6 +159,8 @@ def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn
                 mw.mw_worker_abort(op.a)
             elif k == "wait":
                 wait_all(outstanding, out.status)
+            elif k == "flush":
+                mw.mw_flush()
             elif k == "check":
                 wait_all(outstanding, out.status)
                 if snapshots:
@@ -188,5 +193,9 @@ def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn
             if st == "done" and (o.kind == "recv" or (o.kind not in ("send", "recv") and o.a == 0)):
                 out.payload_bytes_done += o.count * ITEMSIZE[o.dtype]
     finally:
-        mw.mw_shutdown()
+        try:
+            if on_exit is not None:
+                on_exit()
+        finally:
+            mw.mw_shutdown()
     return out

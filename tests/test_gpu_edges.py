@@ -280,6 +280,150 @@ def test_early_completion_is_visible(torch, mw):
     assert early >= 1, "the small message never completed ahead of the large ones"
 
 
+@pytest.mark.parametrize("soff,doff", [(1, 1), (2, 6), (4, 12), (8, 8), (3, 0)])
+def test_early_completion_is_visible_for_every_store_width(torch, mw, soff, doff):
+    """The same for buffers that are not 16-byte aligned: their chunks are moved with 8-, 16-, 32- or 64-bit
+    accesses, whose stores must be as visible at completion as the 128-bit ones."""
+    for w in range(8):
+        mw.mw_world_create(w, [2 * w, 2 * w + 1])
+    big = 256 << 20
+    bsrc = [torch.full((big,), w + 1, dtype=torch.uint8, device="cuda") for w in range(1, 8)]
+    bdst = [torch.zeros(big, dtype=torch.uint8, device="cuda") for _ in range(1, 8)]
+    early = 0
+    for it, small in enumerate([4096 + 2, 65536 + 6, (1 << 20) + 10, 300002]):
+        src = rand_bytes(small, 700 + it)
+        sbase, sview = dev_bytes(torch, src, soff)
+        dbase, dview = dev_bytes(torch, np.full(small, 0xA5, np.uint8), doff)
+        torch.cuda.synchronize()
+        hsmall = [mw.mw_send(0, 0, 1, sview.data_ptr(), small // 2, mw.MW_BF16), mw.mw_recv(0, 0, 1, dview.data_ptr(), small // 2, mw.MW_BF16)]
+        hbig = []
+        for w in range(1, 8):
+            hbig.append(mw.mw_send(w, 0, 1, bsrc[w - 1].data_ptr(), big // 4, mw.MW_F32))
+            hbig.append(mw.mw_recv(w, 0, 1, bdst[w - 1].data_ptr(), big // 4, mw.MW_F32))
+        mw.mw_flush()
+        t0 = time.time()
+        while mw.mw_poll(hsmall[1]) != mw.MW_DONE:
+            assert time.time() - t0 < 30
+        got = dbase.cpu().numpy()  # right away
+        early += any(mw.mw_poll(h) == mw.MW_PENDING for h in hbig)
+        assert np.array_equal(got[doff:doff + small], oracle.copy_result(src)), f"stale bytes in a {small}-byte message"
+        assert np.all(got[:doff] == 0x5A) and np.all(got[doff + small:] == 0x5A)
+        assert wait(mw, hbig) == [mw.MW_DONE] * 14
+    assert early >= 1, "the small message never completed ahead of the large ones"
+
+
+@pytest.mark.parametrize("n", [2, 4])
+def test_early_completion_is_visible_after_a_broadcast(torch, mw, n):
+    """A small broadcast batched with seven large ones in the same fan-out launch."""
+    for w in range(8):
+        mw.mw_world_create(w, list(range(n)))
+    big = 128 << 20
+    bbuf = [[torch.full((big,), (w + 1) * (r == 0), dtype=torch.uint8, device="cuda") for r in range(n)] for w in range(1, 8)]
+    early = 0
+    for it, (small, off) in enumerate([(4096, 0), (65536 + 4, 4), (1 << 20, 0), (4 << 20, 2), (300001 * 4, 1)]):
+        root = it % n
+        host = [rand_bytes(small, 800 + 10 * it + r) for r in range(n)]
+        dev = [dev_bytes(torch, host[r], off) for r in range(n)]
+        torch.cuda.synchronize()
+        hsmall = [mw.mw_broadcast(0, r, root, dev[r][1].data_ptr(), small // 4, mw.MW_F32) for r in range(n)]
+        hbig = [mw.mw_broadcast(w, r, 0, bbuf[w - 1][r].data_ptr(), big // 4, mw.MW_F32) for w in range(1, 8) for r in range(n)]
+        mw.mw_flush()
+        t0 = time.time()
+        while mw.mw_poll(hsmall[0]) != mw.MW_DONE:
+            assert time.time() - t0 < 30
+        got = [dev[r][0].cpu().numpy() for r in range(n)]  # right away
+        early += any(mw.mw_poll(h) == mw.MW_PENDING for h in hbig)
+        want = oracle.broadcast_result(host, root)
+        for r in range(n):
+            assert np.array_equal(got[r][off:off + small], want[r]), f"stale bytes on rank {r} of a {small}-byte broadcast"
+        assert wait(mw, hbig) == [mw.MW_DONE] * (7 * n)
+        for w in range(1, 8):
+            for r in range(1, n):
+                assert bool((bbuf[w - 1][r] == w + 1).all())
+                bbuf[w - 1][r].zero_()
+    assert early >= 1, "the small broadcast never completed ahead of the large ones"
+
+
+@pytest.mark.parametrize("lds", [0, 1])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_early_completion_is_visible_after_an_allreduce(torch, mw, dtype, lds):
+    """A small in-place all-reduce batched with seven large ones in the same launch, register and LDS-staged
+    kernels: every rank's sum must be readable the moment the operation is reported complete."""
+    mw.mw_config_set("reduce_lds", lds)
+    try:
+        n = 3
+        for w in range(8):
+            mw.mw_world_create(w, list(range(n)))
+        isz = 4 if dtype == "f32" else 2
+        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+        big = (96 << 20) // isz
+        bbuf = [[torch.full((big,), float(r + 1), dtype=tdt, device="cuda") for r in range(n)] for _ in range(1, 8)]
+        early = 0
+        for it, (count, off_elems) in enumerate([(1024, 0), (16384 + 3, 1), (262144, 0), (1 << 20, 3), (300001, 2)]):
+            rng = np.random.default_rng(900 + it)
+            xs = [rng.uniform(-1, 1, count).astype(np.float32) for _ in range(n)]
+            host = [x.view(np.uint8) if dtype == "f32" else oracle.f32_to_bf16_bits(x).view(np.uint8) for x in xs]
+            dev = [dev_bytes(torch, host[r], offset=off_elems * isz) for r in range(n)]
+            torch.cuda.synchronize()
+            hsmall = [mw.mw_allreduce_sum(0, r, dev[r][1].data_ptr(), count, mw.DTYPES[dtype]) for r in range(n)]
+            hbig = [mw.mw_allreduce_sum(w, r, bbuf[w - 1][r].data_ptr(), big, mw.DTYPES[dtype]) for w in range(1, 8) for r in range(n)]
+            mw.mw_flush()
+            t0 = time.time()
+            while mw.mw_poll(hsmall[0]) != mw.MW_DONE:
+                assert time.time() - t0 < 30
+            got = [dev[r][1].cpu().numpy() for r in range(n)]  # right away
+            early += any(mw.mw_poll(h) == mw.MW_PENDING for h in hbig)
+            s, sabs = oracle.allreduce_sum_f64(host, count, dtype)
+            ordered = oracle.allreduce_sum_ordered(host, count, dtype)
+            for r in range(n):
+                ok, worst = oracle.allreduce_within_tolerance(got[r], s, sabs, count, dtype)
+                assert ok, (dtype, lds, count, r, worst)
+                assert np.array_equal(got[r], ordered), f"stale bytes on rank {r} of a {count}-element all-reduce"
+            assert wait(mw, hbig) == [mw.MW_DONE] * (7 * n)
+            for w in range(1, 8):
+                for r in range(n):
+                    assert bool((bbuf[w - 1][r] == 6.0).all())  # 1 + 2 + 3, exact in both types
+                    bbuf[w - 1][r].fill_(float(r + 1))
+        assert early >= 1, "the small all-reduce never completed ahead of the large ones"
+    finally:
+        mw.mw_config_set("reduce_lds", 0)
+
+
+def test_a_busy_or_stuck_producer_stream_holds_up_only_its_own_operations(torch, mw):
+    """World A's send is ordered after a long queue of producer kernels on A's stream; world B posts buffers that
+    are final, in the same flush.  B must complete while A is still waiting for its producer (Sec. 3.2: a pending
+    operation in one world must not hold up another), and later flushes of B must not queue behind A either."""
+    mw.mw_world_create(0, [0, 1])
+    mw.mw_world_create(1, [2, 3])
+    n = 1 << 30
+    a_src = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    a_dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    nb = 1 << 20
+    b_host = [rand_bytes(nb, 40 + k) for k in range(3)]
+    b_src = [dev_bytes(torch, h) for h in b_host]
+    b_dst = [dev_bytes(torch, np.full(nb, 0xA5, np.uint8)) for _ in range(3)]
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        for k in range(1, 121):  # ~0.3 ms each: the producer is busy for tens of milliseconds
+            a_src.fill_(k % 251)
+    ha = [mw.mw_send(0, 0, 1, a_src.data_ptr(), n // 4, mw.MW_F32, s.cuda_stream),
+          mw.mw_recv(0, 0, 1, a_dst.data_ptr(), n // 4, mw.MW_F32, mw.STREAM_NONE)]
+    a_pending_seen = 0
+    for k in range(3):  # the first shares A's flush, the others come in flushes of their own
+        hb = [mw.mw_send(1, 0, 1, b_src[k][1].data_ptr(), nb // 4, mw.MW_F32, mw.STREAM_NONE),
+              mw.mw_recv(1, 0, 1, b_dst[k][1].data_ptr(), nb // 4, mw.MW_F32, mw.STREAM_NONE)]
+        mw.mw_flush()
+        t0 = time.time()
+        while mw.mw_poll(hb[1]) != mw.MW_DONE:
+            assert time.time() - t0 < 30
+        a_pending_seen += mw.mw_poll(ha[1]) == mw.MW_PENDING
+        assert np.array_equal(b_dst[k][1].cpu().numpy(), oracle.copy_result(b_host[k]))
+    assert a_pending_seen == 3, "world B's transfers should all have completed while world A waited for its producer"
+    assert wait(mw, ha) == [mw.MW_DONE] * 2
+    assert bool((a_dst == 120 % 251).all())  # ordered after the LAST producer kernel
+
+
 def test_post_is_ordered_after_the_callers_stream(torch, mw):
     mw.mw_world_create(0, [0, 1])
     n = 64 << 20

@@ -89,3 +89,49 @@ def test_config5_small_statuses_follow_the_fault_closed_form(host_pools):
     assert aborts_seen == 3
     assert set(r.status.values()) == {DONE, BROKEN}
     assert len(r.snapshots) > 600
+
+
+def test_online_recovery_trace_breaks_exactly_the_failed_workers_worlds(host_pools):
+    """Fig. 2 in small: the statuses follow from the scenario alone (P3 = worker 2 fails; worlds 2 and 4 contain
+    it), and every delivered tensor is its source (buffers are created src, dst per message; orphan receives
+    have a destination only)."""
+    t = workloads.online_recovery(count=257, window=4, rounds=2)
+    r = run_trace(t, _mat(host_pools))
+    assert r.world_state == {1: "alive", 3: "alive", 2: BROKEN, 4: BROKEN, 6: "alive", 7: "alive"}
+    failed_at = next(i for i, op in enumerate(t.ops) if op.kind == "abort_worker")
+    assert t.ops[failed_at].a == 2
+    sends = {}  # destination buffer -> source buffer, from the way the generator pairs them
+    for i, op in enumerate(t.ops):
+        if i not in r.status:
+            continue
+        in_p3_world = op.world in (2, 4)
+        if in_p3_world and i > failed_at:
+            assert r.status[i] == BROKEN  # refused
+        elif op.kind == "recv" and t.bufs[op.buf - 1].init[0] == "fill":
+            assert in_p3_world and r.status[i] == BROKEN  # the orphan receive: its tensor never came
+        else:
+            assert r.status[i] == DONE, (i, op)
+            if op.kind == "recv":
+                sends[op.buf] = op.buf - 1
+    assert sum(1 for s in r.status.values() if s == BROKEN) == 2 + 2 * 2 * 4
+    delivered = 0
+    for i, op in enumerate(t.ops):
+        if op.kind != "check":
+            continue
+        if op.buf in sends:
+            assert np.array_equal(r.snapshots[i], materialize(t.bufs[sends[op.buf]]))
+            delivered += 1
+        else:
+            assert np.all(r.snapshots[i] == 0xA5)  # nothing was written where nothing was delivered
+    assert delivered == len(sends) == (3 * 2 + 2 * 4 + 4 + 2 + 2 + 2 * 4) * 4
+
+
+def test_multi_sender_traces_deliver_every_tensor_in_both_setups(host_pools):
+    for senders in (1, 2, 3):
+        for multi in (True, False):
+            t = workloads.multi_sender(senders, 1000, multi, window=4, n_windows=2)
+            r = run_trace(t, _mat(host_pools))
+            assert all(s == DONE for s in r.status.values()) and len(r.status) == 2 * senders * 8
+            for i, op in enumerate(t.ops):
+                if op.kind == "check":
+                    assert np.array_equal(r.snapshots[i], materialize(t.bufs[op.buf - 1]))

@@ -15,5 +15,7 @@ from .configs import (  # noqa: F401
     config4,
     config5,
     collectives_mix,
+    online_recovery,
+    multi_sender,
     single_world_of,
 )

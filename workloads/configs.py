@@ -392,6 +392,106 @@ def collectives_mix(n_ops=400, n_worlds=12, n_workers=16, min_bytes=64, max_byte
 
 
 # ---------------------------------------------------------------------------
+# online instantiation and recovery under load (the paper's Sec. 3.1 / Fig. 2 and Sec. 4.2 / Fig. 5 in shape)
+# ---------------------------------------------------------------------------
+def online_recovery(count=1_000_000, window=4, rounds=2):
+    """The rhombus of Fig. 2: P1 -> {P2, P3} -> P4 with one world per edge, fp32 tensors of `count` elements
+    (4 MB in Sec. 4.2).  Workers 0..3 are P1..P4, worker 4 is the replacement P5.
+
+      phase 1  only the P2 path exists (worlds 1 = (P1,P2), 3 = (P2,P4)) and streams windows;
+      phase 2  with a window of the P2 path in flight, worlds 2 = (P1,P3) and 4 = (P3,P4) are created
+               (online instantiation) and all four worlds stream;
+      phase 3  a window is posted in all four worlds, the P3 worlds also get receives whose tensors never
+               come; with that window in flight P3 fails: what was matched is delivered, the rest is broken,
+               later posts to its worlds are refused, the P2 path streams on;
+      phase 4  with a window of the P2 path in flight, P5 takes P3's place through two NEW worlds
+               6 = (P1,P5) and 7 = (P5,P4) (Fig. 2(c)); all healthy worlds stream.
+
+    Every destination is checked."""
+    t = Trace("online_recovery", n_workers=5, n_streams=2)
+    sd = _Seeds(7)
+    dsts = []
+
+    def window_of(worlds, orphans=()):
+        """One window: `window` messages rank 0 -> rank 1 in each of `worlds`; `orphans` get one recv more."""
+        for j in range(window):
+            for w in worlds:
+                src = t.tensor(count, "f32", _payload_init("normal", "f32", count, sd))
+                dst = t.tensor(count, "f32", ("fill", POISON))
+                dsts.append(dst)
+                if j % 2:
+                    t.recv(w, 0, 1, dst, count, "f32", stream=w % 2)
+                    t.send(w, 0, 1, src, count, "f32", stream=w % 2)
+                else:
+                    t.send(w, 0, 1, src, count, "f32", stream=w % 2)
+                    t.recv(w, 0, 1, dst, count, "f32", stream=w % 2)
+        for w in orphans:
+            dst = t.tensor(count, "f32", ("fill", POISON))
+            dsts.append(dst)
+            t.recv(w, 0, 1, dst, count, "f32", stream=w % 2)
+
+    t.create(1, (0, 1))
+    t.create(3, (1, 3))
+    for _ in range(rounds):
+        window_of((1, 3))
+        t.wait()
+    window_of((1, 3))
+    t.flush()
+    t.create(2, (0, 2))  # while the window above is in flight
+    t.create(4, (2, 3))
+    for _ in range(rounds):
+        window_of((1, 2, 3, 4))
+        t.wait()
+    window_of((1, 2, 3, 4), orphans=(2, 4))
+    t.flush()
+    t.abort_worker(2)  # P3
+    window_of((1, 2, 3, 4))  # worlds 2 and 4 refuse
+    t.wait()
+    window_of((1, 3))
+    t.flush()
+    t.create(6, (0, 4))  # P5 joins through new worlds while the P2 path has a window in flight
+    t.create(7, (4, 3))
+    for _ in range(rounds):
+        window_of((1, 3, 6, 7))
+        t.wait()
+    for d in dsts:
+        t.check(d)
+    t.meta.update(count=count, window=window, rounds=rounds)
+    return t
+
+
+# ---------------------------------------------------------------------------
+# the multi-sender experiment in shape (Sec. 4.3 / Fig. 7)
+# ---------------------------------------------------------------------------
+def multi_sender(senders, count, multi_world, window=8, n_windows=2):
+    """`senders` workers (1..3) each send fp32 tensors of `count` elements to worker 0, `window` messages per
+    sender outstanding together.  multi_world: one world per sender, (receiver, sender k), the receiver in all of
+    them; otherwise one world holding the receiver and every sender."""
+    t = Trace(f"multi_sender_{senders}_{count}_{'mw' if multi_world else 'sw'}", n_workers=senders + 1, n_streams=senders)
+    sd = _Seeds(8 + senders)
+    if multi_world:
+        for k in range(senders):
+            t.create(k, (0, 1 + k))
+    else:
+        t.create(0, tuple(range(senders + 1)))
+    dsts = []
+    for _ in range(n_windows):
+        for j in range(window):
+            for k in range(senders):
+                w, a = (k, 1) if multi_world else (0, 1 + k)
+                src = t.tensor(count, "f32", _payload_init("normal", "f32", count, sd))
+                dst = t.tensor(count, "f32", ("fill", POISON))
+                dsts.append(dst)
+                t.recv(w, a, 0, dst, count, "f32", stream=k)
+                t.send(w, a, 0, src, count, "f32", stream=k)
+        t.wait()
+    for d in dsts:
+        t.check(d)
+    t.meta.update(senders=senders, count=count, multi_world=multi_world)
+    return t
+
+
+# ---------------------------------------------------------------------------
 # single-world baseline of a point-to-point trace
 # ---------------------------------------------------------------------------
 def single_world_of(trace, drop_aborts=True):

@@ -6,7 +6,9 @@ Buffers are referred to by integer id; a buffer comes into existence with its
 spec's initial bytes the first time an operation names it and lives until a
 "free" operation.  "wait" asks the runner to let everything outstanding reach
 a terminal state (the reference semantics are sequential, so it means nothing
-there); "check" asks for a snapshot of a buffer at that point of the trace;
+there); "flush" asks it to start what can be started without waiting for it
+(likewise nothing there): what follows in the trace then happens while those
+operations are in flight; "check" asks for a snapshot of a buffer at that point of the trace;
 "restore" rewrites a buffer with its initial bytes.
 """
 
@@ -21,7 +23,7 @@ POSTING = ("send", "recv", "bcast", "allreduce", "reduce", "allgather", "gather"
 
 @dataclass
 class Op:
-    kind: str  # create send recv bcast allreduce abort_world abort_worker wait check restore free
+    kind: str  # create send recv bcast allreduce ... abort_world abort_worker wait flush check restore free
     world: int = -1
     a: int = -1  # p2p: src rank; collectives: posting rank; abort_worker: worker id
     b: int = -1  # p2p: dst rank; bcast: root rank
@@ -92,6 +94,9 @@ class Trace:
 
     def wait(self):
         return self.add(Op("wait"))
+
+    def flush(self):
+        return self.add(Op("flush"))
 
     def check(self, buf):
         return self.add(Op("check", buf=buf))
