@@ -219,6 +219,32 @@ typedef struct {
 } mw_post_desc;
 int mw_post_many(const mw_post_desc* posts, int n, mw_handle* handles, int* results);
 
+/* For callers that cannot allocate or wait on the host: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  A variant of mw_post_many that allocates nothing, on the device or on the
+ * host, and hands out no handles: the array must hold WHOLE operations (every side of each), which are matched by
+ * the same rules as everywhere else (first in, first out per (world, src, dst); the k-th collective a rank posts
+ * in a world belongs to that world's k-th collective), independently of sides posted through the other calls,
+ * whose queues are neither read nor changed.  All of them are enqueued on `hip_stream` (hipStream_t as void*,
+ * NULL = the null stream; MW_STREAM_NONE is refused) behind whatever that stream already holds, and they are
+ * complete when work enqueued on that stream afterwards runs: completion is by stream order, there is nothing to
+ * poll.  The posts' own hip_stream fields are ignored.  The operations of one call run concurrently: apart from
+ * buffers that are only read, they must not share bytes.
+ *
+ * The kernels are the ones every other call uses; their per-operation completion state (arrival counter,
+ * completion word: device memory beyond the callers' buffers) lives in a static device array of
+ * MW_NOALLOC_MAX_OPS slots (16.25 KiB per GPU, held until the process ends) instead of the ring arena, and is
+ * re-armed by a small fill kernel at the start of every call (no memset node: the call may be recorded into a
+ * graph).  Every call on a GPU shares that array: two calls whose kernels overlap in time on one GPU race on it --
+ * issue them on one stream, or order them with events.
+ *
+ * At most MW_NOALLOC_MAX_POSTS posts forming at most MW_NOALLOC_MAX_OPS operations that move data: MW_EINVAL
+ * beyond that, for a side whose peers are not all in the array, and for whatever the posting calls refuse;
+ * MW_ENOWORLD / MW_EBROKEN for an unknown / broken world; MW_EMISMATCH if the sides of an operation disagree.  On
+ * any error nothing has been enqueued.  Needs mw_init (which does allocate) to have been called. */
+#define MW_NOALLOC_MAX_POSTS 128
+#define MW_NOALLOC_MAX_OPS 64
+int mw_post_many_noalloc(const mw_post_desc* posts, int n, void* hip_stream);
+
 /* Number of operations that have all their sides posted and have not yet been seen complete by a
  * poll (queued for launch or in flight).  0 means every remaining MW_PENDING handle waits for a peer. */
 int mw_pending_ops(void);

@@ -31,7 +31,7 @@ SYMBOLS = [
     "mw_config_set", "mw_config_get", "mw_handle_capacity", "mw_last_hip_error", "mw_strerror",
     "mw_profile_enable", "mw_profile_read", "mw_debug_ring_read", "mw_debug_arena_hash", "mw_heartbeat",
     "mw_heartbeat_at", "mw_watchdog_start", "mw_watchdog_stop", "mw_watchdog_check_at", "mw_worker_state",
-    "mw_heartbeat_epoch", "mw_build_id",
+    "mw_heartbeat_epoch", "mw_build_id", "mw_post_many_noalloc",
 ]
 
 
@@ -76,6 +76,7 @@ def declare(lib):
     lib.mw_pending_ops.argtypes = []
     lib.mw_poll_many.argtypes = [u64p, i, C.POINTER(C.c_int)]
     lib.mw_post_many.argtypes = [C.POINTER(PostDesc), i, u64p, C.POINTER(C.c_int)]
+    lib.mw_post_many_noalloc.argtypes = [C.POINTER(PostDesc), i, vp]
     lib.mw_config_set.argtypes = [C.c_char_p, C.c_long]
     lib.mw_config_get.argtypes = [C.c_char_p]
     lib.mw_config_get.restype = C.c_long
@@ -272,6 +273,13 @@ def mw_post_many(posts):
     pb = PostBatch(posts)
     pb.post(check=False)
     return list(pb.handles), list(pb.results)
+
+
+def mw_post_many_noalloc(posts, stream=0):
+    """Enqueue whole operations on `stream` without allocating; `posts` is a PostBatch or a list of post tuples.
+    Returns the library's code (negative = refused, nothing enqueued)."""
+    pb = posts if isinstance(posts, PostBatch) else PostBatch(posts)
+    return lib().mw_post_many_noalloc(pb.descs, pb.n, _stream(stream))
 
 
 def mw_poll_many(handles):

@@ -30,8 +30,19 @@
 #include "../../include/mw.h"
 #include "mw_internal.hpp"
 
+// Scratch of the entry point that allocates nothing (mw_post_many_noalloc): ring slots (arrival counter and
+// completion word per operation) followed by the completion words the kernels otherwise write to host-pinned
+// memory.  One copy per GPU, held until the process ends; every call on a GPU shares it, so calls that overlap
+// on one GPU race.  Host code never uses this name as an address: the per-device address comes from
+// hipGetSymbolAddress at init (g_scratch_ptr).
+static __device__ __align__(256) unsigned char scratch[MW_NOALLOC_MAX_OPS * (mw::kSlotBytes + 4)];
+constexpr int kMaxHipDevices = 64;
+static unsigned char* g_scratch_ptr[kMaxHipDevices] = {};  // device address of `scratch`, per HIP device
+
 namespace mw {
 namespace {
+
+constexpr int kStaticOps = MW_NOALLOC_MAX_OPS;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -564,6 +575,11 @@ __global__ __launch_bounds__(64) void mw_k_mark(RingHeader* __restrict__ dst, co
   reinterpret_cast<uint32_t*>(dst)[threadIdx.x] = w[threadIdx.x];
 }
 
+// Re-arm the arrival counters of the first n static slots (the static array keeps the last call's contents).
+__global__ __launch_bounds__(kStaticOps) void mw_k_clear(RingSlot* __restrict__ slots, uint32_t n) {
+  if (threadIdx.x < n) __hip_atomic_store(&slots[threadIdx.x].s.arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // ------------------------------------------------------------------------------------------------
 // host side of the backend
 // ------------------------------------------------------------------------------------------------
@@ -655,6 +671,28 @@ class HipDevice : public Device {
       rc = launch_group(ops, n, (int)g);
     }
     return rc;
+  }
+
+  int launch_static(const LaunchOp* ops, int n, void* stream) override {
+    if (n < 0 || n > kStaticOps) return fail_inval();
+    if (chk(hipSetDevice(dev_))) return MW_EHIP;
+    if (!static_base_) return fail_inval();
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    RingSlot* sslots = reinterpret_cast<RingSlot*>(static_base_);
+    uint32_t* sflags = reinterpret_cast<uint32_t*>(static_base_ + (size_t)kStaticOps * sizeof(RingSlot));
+    if (n == 0) return MW_OK;
+    // The array keeps the previous call's contents: the arrival counters must start at zero.  A fill kernel,
+    // not a memset node, so that the call may be recorded into a graph.
+    hipLaunchKernelGGL(mw_k_clear, dim3(1), dim3(kStaticOps), 0, st, sslots, (uint32_t)n);
+    if (chk(hipGetLastError())) return MW_EHIP;
+    static_launched_.assign((size_t)n, 0);  // capacity reserved at init: no allocation
+    launched_ = static_launched_.data();
+    cur_slots_ = sslots;
+    cur_flags_ = sflags;
+    host_flags_ok_ = false;
+    group_of_.assign((size_t)n, -1);
+    for (uint32_t k = 0; k < kNumKinds; ++k) data_[k] = st;
+    return run_group(ops, n, -1);
   }
 
   int mark_world(uint32_t ring_index, const RingHeader& h) override {
@@ -755,13 +793,24 @@ class HipDevice : public Device {
     if (chk(hipFuncSetAttribute(reinterpret_cast<const void*>(&mw_k_reduce<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kMaxBufs * kReduceWG * 16)))
       return MW_EHIP;
-    // Host tables sized once, so that launching never grows them.
+    // The static scratch of the entry point that allocates nothing: each GPU holds its own copy of the array at
+    // its own address, looked up once per device with that device current.
+    if (hip_device < kMaxHipDevices && g_scratch_ptr[hip_device]) {
+      static_base_ = g_scratch_ptr[hip_device];
+    } else {
+      unsigned char* ptr = nullptr;
+      if (chk(hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch))) || !ptr) return MW_EHIP;
+      if (hip_device < kMaxHipDevices) g_scratch_ptr[hip_device] = ptr;
+      static_base_ = ptr;
+    }
+    // Host tables sized once, so that launching never grows them (the no-allocation entry point relies on it).
     ents_.reserve(512);
     one_.reserve(64);
     chunks_.reserve(512);
     op_chunks_.reserve(512);
     chunk_bytes_.reserve(512);
     group_of_.reserve(4096);
+    static_launched_.reserve(kStaticOps);
     if (chk(hipDeviceSynchronize())) return MW_EHIP;
     ready_ = true;
     return MW_OK;
@@ -1100,8 +1149,10 @@ class HipDevice : public Device {
   std::vector<Ent> ents_, one_;
   uint8_t* launched_ = nullptr;  // the current launch() call's per-operation result array
   RingSlot* cur_slots_ = nullptr;   // where the current launch's kernels count chunks in and publish completion:
-  uint32_t* cur_flags_ = nullptr;   // the arena and the host-pinned words
+  uint32_t* cur_flags_ = nullptr;   // the arena and the host-pinned words, or the static scratch
   bool host_flags_ok_ = true;       // the current launch publishes to the host-pinned words
+  unsigned char* static_base_ = nullptr;  // device address of `scratch` on dev_
+  std::vector<uint8_t> static_launched_;
   std::vector<void*> dep_streams_, waited_;  // distinct caller streams of the current launch() call
   std::vector<uint8_t> dep_busy_;            // ... and whether each still had work pending
   std::vector<int> group_of_;                // per operation: index of its first busy stream, or -1

@@ -66,6 +66,14 @@ class NullDevice : public Device {
     }
     return MW_OK;
   }
+  int launch_static(const LaunchOp* ops, int n, void*) override {
+    std::lock_guard<std::mutex> g(st_.mu);
+    int id = (int)st_.launch_sizes.size();
+    st_.launch_sizes.push_back(n);
+    st_.launch_streams.push_back(1);
+    for (int i = 0; i < n; ++i) st_.log.push_back(Recorded{ops[i], id});  // complete by stream order: never pending
+    return MW_OK;
+  }
   int mark_world(uint32_t ring_index, const RingHeader& h) override {
     std::lock_guard<std::mutex> g(st_.mu);
     st_.headers[ring_index] = h;

@@ -113,6 +113,8 @@ struct Context {
   std::vector<uint8_t> beating;      // worker has sent at least one heartbeat: it is being watched
   std::vector<uint8_t> failed;       // the watchdog has declared the worker failed
 
+  uint32_t noalloc_gen = 0;  // generation of the latest mw_post_many_noalloc call
+
   std::vector<LaunchOp> launch_buf;
   std::vector<OpDeps> deps_buf;
   std::vector<uint32_t> launched_buf;
@@ -823,6 +825,138 @@ int mw_post_many(const mw_post_desc* posts, int n, mw_handle* handles, int* resu
     if (rc != MW_OK && first_err == MW_OK) first_err = rc;
   }
   return first_err;
+}
+
+int mw_post_many_noalloc(const mw_post_desc* posts, int n, void* hip_stream) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  Context& c = *g_ctx;
+  if (n < 0 || n > MW_NOALLOC_MAX_POSTS || (n > 0 && !posts) || hip_stream == MW_STREAM_NONE) return MW_EINVAL;
+  // Everything below lives on the stack: no table of the context is touched, nothing is allocated.
+  LaunchOp ops[MW_NOALLOC_MAX_OPS];
+  int n_ops = 0;
+  bool used[MW_NOALLOC_MAX_POSTS] = {};
+  uint32_t seq[MW_NOALLOC_MAX_POSTS] = {};  // collectives: which collective of its (world, rank) a post is
+  const World* world_of[MW_NOALLOC_MAX_POSTS] = {};
+  for (int i = 0; i < n; ++i) {  // validate every post as its posting call would
+    const mw_post_desc& p = posts[i];
+    if (p.kind < MW_POST_SEND || p.kind > MW_POST_SCATTER) return MW_EINVAL;
+    if (p.dtype != MW_F32 && p.dtype != MW_BF16) return MW_EINVAL;
+    auto it = c.world_of_id.find(p.world_id);
+    if (it == c.world_of_id.end()) return MW_ENOWORLD;
+    const World& w = *c.worlds[it->second];
+    world_of[i] = &w;
+    const int nr = (int)w.members.size();
+    if (p.count > (SIZE_MAX >> 6)) return MW_EINVAL;
+    if (p.kind <= MW_POST_RECV) {
+      if (p.a < 0 || p.b < 0 || p.a >= nr || p.b >= nr || p.a == p.b) return MW_EINVAL;
+      if (p.count > 0 && !p.buf) return MW_EINVAL;
+    } else {
+      const uint32_t k = (uint32_t)p.kind - MW_POST_BROADCAST + opBcast;  // the two enums run in the same order
+      if (nr > MW_MAX_COLL_RANKS || p.a < 0 || p.a >= nr) return MW_EINVAL;
+      if (rooted(k) && (p.b < 0 || p.b >= nr)) return MW_EINVAL;
+      const int root = rooted(k) ? p.b : 0;
+      if (p.count > 0) {
+        const bool need1 = k != opScatter || p.a == root;
+        const bool need2 = k == opAllGather || k == opScatter || (k == opGather && p.a == root);
+        if ((need1 && !p.buf) || (need2 && !p.buf2)) return MW_EINVAL;
+      }
+      if ((k == opAllReduce || k == opReduce) && ((uintptr_t)p.buf % item_size((uint32_t)p.dtype)) != 0) return MW_EINVAL;
+      for (int j = 0; j < i; ++j)
+        seq[i] += posts[j].kind > MW_POST_RECV && posts[j].world_id == p.world_id && posts[j].a == p.a;
+    }
+    if (w.state == MW_BROKEN) return MW_EBROKEN;
+  }
+  for (int i = 0; i < n; ++i) {
+    if (used[i]) continue;
+    const mw_post_desc& p = posts[i];
+    const World& w = *world_of[i];
+    const int nr = (int)w.members.size();
+    LaunchOp l{};
+    l.dtype = (uint32_t)p.dtype;
+    l.nbytes = p.count * item_size((uint32_t)p.dtype);
+    l.world_id = (uint32_t)w.id;
+    l.world_epoch = w.epoch;
+    bool moves = p.count > 0;
+    if (p.kind <= MW_POST_RECV) {
+      // first in, first out per (world, src, dst): this side pairs with the earliest later side of the other kind
+      // that no earlier side has taken
+      int j = i + 1;
+      while (j < n && !(!used[j] && posts[j].kind == 1 - p.kind && posts[j].world_id == p.world_id &&
+                        posts[j].a == p.a && posts[j].b == p.b))
+        ++j;
+      if (j == n) return MW_EINVAL;  // a side without its peer: this call takes whole operations only
+      used[i] = used[j] = true;
+      if (posts[j].count != p.count || posts[j].dtype != p.dtype) return MW_EMISMATCH;
+      const mw_post_desc& snd = p.kind == MW_POST_SEND ? p : posts[j];
+      const mw_post_desc& rcv = p.kind == MW_POST_SEND ? posts[j] : p;
+      l.kind = opCopy;
+      l.nbuf = 2;
+      l.buf[0] = (uint64_t)(uintptr_t)snd.buf;
+      l.buf[1] = (uint64_t)(uintptr_t)rcv.buf;
+    } else {
+      const uint32_t k = (uint32_t)p.kind - MW_POST_BROADCAST + opBcast;
+      const int root = rooted(k) ? p.b : 0;
+      int side[kMaxBufs];
+      for (int r = 0; r < nr; ++r) side[r] = -1;
+      for (int j = i; j < n; ++j)
+        if (!used[j] && posts[j].kind > MW_POST_RECV && posts[j].world_id == p.world_id && seq[j] == seq[i] &&
+            side[posts[j].a] < 0)
+          side[posts[j].a] = j;
+      for (int r = 0; r < nr; ++r) {
+        if (side[r] < 0) return MW_EINVAL;  // a rank did not post this collective
+        used[side[r]] = true;
+      }
+      for (int r = 0; r < nr; ++r) {
+        const mw_post_desc& q = posts[side[r]];
+        const int qroot = rooted(k) ? q.b : 0;
+        if (q.kind != p.kind || qroot != root || q.count != p.count || q.dtype != p.dtype) return MW_EMISMATCH;
+      }
+      l.kind = k;
+      l.nbuf = (uint32_t)nr;
+      l.root = (uint32_t)root;
+      auto b1 = [&](int r) { return (uint64_t)(uintptr_t)posts[side[r]].buf; };
+      auto b2 = [&](int r) { return (uint64_t)(uintptr_t)posts[side[r]].buf2; };
+      switch (k) {
+        case opBcast: {
+          int at = 0;
+          l.buf[at++] = b1(root);
+          for (int r = 0; r < nr; ++r)
+            if (r != root) l.buf[at++] = b1(r);
+          break;
+        }
+        case opAllReduce:
+        case opReduce:
+          for (int r = 0; r < nr; ++r) l.buf[r] = b1(r);
+          break;
+        case opAllGather:
+          for (int r = 0; r < nr; ++r) {
+            l.buf[r] = b1(r);
+            l.buf[8 + r] = b2(r);
+          }
+          break;
+        case opGather:
+          for (int r = 0; r < nr; ++r) l.buf[r] = b1(r);
+          l.buf[8] = b2(root);
+          break;
+        default:  // opScatter
+          l.buf[0] = b1(root);
+          for (int r = 0; r < nr; ++r) l.buf[8 + r] = b2(r);
+          break;
+      }
+      const bool moves_alone = k == opAllGather || k == opGather || k == opScatter;
+      if (nr == 1 && (!moves_alone || p.buf == p.buf2)) moves = false;
+    }
+    if (!moves) continue;
+    if (n_ops == MW_NOALLOC_MAX_OPS) return MW_EINVAL;
+    l.slot = (uint32_t)n_ops;
+    ops[n_ops++] = l;
+  }
+  // One generation per call, shared by its operations (their slots differ); never 0.
+  c.noalloc_gen += 1;
+  if (c.noalloc_gen == 0) c.noalloc_gen = 1;
+  for (int i = 0; i < n_ops; ++i) ops[i].gen = c.noalloc_gen;
+  return c.dev->launch_static(ops, n_ops, hip_stream);
 }
 
 int mw_poll(mw_handle h) {

@@ -120,6 +120,9 @@ class Device {
   // Returns 0 or MW_EHIP; launched[i] is set to 1 for every operation that was enqueued on the device (all
   // of them on success; on failure the others were not and may be retried).
   virtual int launch(const LaunchOp* ops, const OpDeps* deps, int n, uint8_t* launched) = 0;
+  // Enqueue `n` <= MW_NOALLOC_MAX_OPS operations on the caller's stream with their completion state in the static
+  // device scratch (slot = index of the operation); allocates nothing, publishes nothing to the host.
+  virtual int launch_static(const LaunchOp* ops, int n, void* stream) = 0;
   // Write a ring header (world create / abort marker).  Asynchronous, on the library's stream.
   virtual int mark_world(uint32_t ring_index, const RingHeader& h) = 0;
   // Host-visible completion word of a slot (acquire load of the pinned mirror).
