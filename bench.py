@@ -53,6 +53,8 @@ def parse():
     ap.add_argument("--depth", type=int, default=2, help="config5: windows in flight (window x depth <= 64)")
     ap.add_argument("--chunk-bytes", type=int, default=0, help="pin the kernels' chunk size (0 = chosen per launch)")
     ap.add_argument("--reduce-lds", type=int, default=0, help="config3: 1 = LDS-staged all-reduce kernel")
+    ap.add_argument("--coll-launches", type=int, default=200, help="collectives: timed launches per operation")
+    ap.add_argument("--coll-warmup", type=int, default=20, help="collectives: untimed launches per operation")
     ap.add_argument("--shape", type=int, nargs=3, default=list(SHAPE), help=argparse.SUPPRESS)
     return ap.parse_args()
 
@@ -321,6 +323,48 @@ def _profile(mw, kind):
     return launches, ms, op_bytes
 
 
+KERNEL_NAME = {0: "mw_k_copy", 1: "mw_k_bcast", 2: "mw_k_reduce"}
+
+
+def roofline(kernel, alg_bytes_total, launches, kernel_ms, traffic=None, note=None):
+    """Roofline object of one kernel: algorithmic bytes of its launches over their summed duration (HIP events on
+    the stream the kernel ran on), against the 8 TB/s HBM peak."""
+    launches = max(int(launches), 1)
+    avg_ms = kernel_ms / launches
+    achieved = alg_bytes_total / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
+    out = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+           "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "launches": launches,
+           "avg_launch_ms": round(avg_ms, 5), "alg_bytes_per_launch": round(alg_bytes_total / launches)}
+    if note:
+        out["note"] = note
+    return out
+
+
+def oracle_on_trace(trace, sample, all_data=True):
+    """The CPU oracle on a trace, one thread; drawing the inputs is not counted.  Returns the cpu_baseline object
+    (payload GB/s of the operations that completed)."""
+    from oracle.run_trace import run_trace as run_oracle
+    from workloads import HostPools, materialize
+
+    pools = HostPools()
+    for dt in ("f32", "bf16"):
+        pools.get(dt)
+    drawing = [0.0]
+
+    def mat(spec):
+        t0 = time.perf_counter()
+        r = materialize(spec, pools)
+        drawing[0] += time.perf_counter() - t0
+        return r
+
+    t0 = time.perf_counter()
+    run = run_oracle(trace, mat, data_bufs=set(trace.bufs) if all_data else None)
+    secs = time.perf_counter() - t0 - drawing[0]
+    return {"value": round(run.payload_bytes_done / secs / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{sample}; {run.payload_bytes_done / 1e6:.1f} MB of payload in {secs:.2f} s of oracle time (drawing the "
+                      f"inputs, {drawing[0]:.1f} s, not counted); host has {os.cpu_count()} logical CPUs"}
+
+
 def run_config4(torch, mw, dev, steps, abort_step, reps):
     """Elastic fan-in: 16 producers -> one shared consumer, 160 MiB bf16 messages, producer 7 aborted
     before step `abort_step`; its world keeps being attempted (and refused) afterwards."""
@@ -575,6 +619,13 @@ def run_config1(torch, mw, dev, reps):
             pass
         rt.append(time.perf_counter() - t0)
     rt.sort()
+    # kernel time in a pass of its own: the event records would cost a good part of a ~10 us window
+    mw.mw_profile_enable(True)
+    mw.mw_profile_read(mw.KIND_COPY)
+    for _ in range(8):
+        run(multi)
+    launches, kernel_ms, op_bytes = mw.mw_profile_read(mw.KIND_COPY)
+    mw.mw_profile_enable(False)
     mean = lambda v: sum(v) / len(v)
     secs = mean(mw_t)
     value = n_msgs * count * 4 / secs / 1e9
@@ -589,7 +640,9 @@ def run_config1(torch, mw, dev, reps):
                                          "p90": round(rt[9 * len(rt) // 10] * 1e6, 2)},
         "single_world_GBps": round(n_msgs * count * 4 / mean(sw_t) / 1e9, 3),
         "loss_vs_single_world_pct": round((1 - mean(sw_t) / mean(mw_t)) * 100, 3),
-        "roofline": None,
+        "roofline": roofline("mw_k_copy", 2 * op_bytes, launches, kernel_ms,
+                             note="latency-bound: one launch moves a window of 16 messages of 32 KiB (1 MiB of traffic, 0.13 us at "
+                                  "the HBM peak), the launch itself takes several us; measured in a separate pass with event records"),
     }
 
 
@@ -689,6 +742,7 @@ def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
 
     # payload of the operations that complete: everything posted to a world that is still alive
     dead, payload, alg = set(), 0, 0
+    alg_kind = {mw.KIND_COPY: 0, mw.KIND_BCAST: 0, mw.KIND_REDUCE: 0}
     for op in t.ops:
         if op.kind == "abort_worker":
             dead.add(op.a)
@@ -697,16 +751,32 @@ def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
             n = len(members[op.world])
             if op.kind == "recv":
                 payload += S
-                alg += 2 * S
+                alg_kind[mw.KIND_COPY] += 2 * S
             elif op.kind == "bcast" and op.a == 0:
                 payload += S
-                alg += n * S
+                alg_kind[mw.KIND_BCAST] += n * S
             elif op.kind == "allreduce" and op.a == 0:
                 payload += S
-                alg += 2 * n * S
+                alg_kind[mw.KIND_REDUCE] += 2 * n * S
+    alg = sum(alg_kind.values())
     run(10_000)  # warm-up (worker aborts only break this pass's worlds)
     times = [run(10_000 * (i + 2)) for i in range(max(reps, 1))]
     secs = sum(times) / len(times)
+    # one more pass with every launch bracketed by events: kernel time per kind (the three kinds run on streams
+    # of their own and overlap, so their times add up to more than the wall time they share)
+    mw.mw_profile_enable(True)
+    for k in alg_kind:
+        mw.mw_profile_read(k)
+    secs_profiled = run(5_000_000)
+    kinds = {}
+    for k in alg_kind:
+        launches, ms, _ = mw.mw_profile_read(k)
+        kinds[KERNEL_NAME[k]] = roofline(KERNEL_NAME[k], alg_kind[k], launches, ms)
+        kinds[KERNEL_NAME[k]]["kernel_ms_total"] = round(ms, 3)
+    mw.mw_profile_enable(False)
+    roof = dict(kinds["mw_k_copy"])
+    roof["note"] = ("dominant kernel by bytes; the copy, fan-out and reduce launches of a window overlap on separate streams, so each "
+                    "kernel's own rate is what it gets of the bandwidth they share; all kernels together: roofline_overall")
     # single-world comparison on the send/recv subset (collectives change meaning in a bigger world, and one
     # worker abort would end the single world): the same messages in the same order, no aborts on either side
     p2p_payload = sum(op.count * (4 if op.dtype == "f32" else 2) for op in t.ops if op.kind == "recv")
@@ -724,19 +794,47 @@ def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
         "p2p_subset_single_world_GBps": round(p2p_payload / (sum(sw_t) / len(sw_t)) / 1e9, 1) if reps else None,
         "p2p_subset_multi_world_GBps": round(p2p_payload / (sum(mw_t) / len(mw_t)) / 1e9, 1) if reps else None,
         "loss_vs_single_world_pct": round((1 - (sum(sw_t) / len(sw_t)) / (sum(mw_t) / len(mw_t))) * 100, 3) if reps else None,
-        "roofline": None,
+        "roofline": roof, "roofline_per_kernel": kinds,
+        "roofline_overall": {"bound": "hbm", "achieved": round(alg / secs / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                             "frac": round(alg / secs / 1e9 / HBM_PEAK_GBPS, 4),
+                             "note": "all algorithmic bytes of the pass over its wall time (launch gaps and host polling included)"},
+        "wall_ms_of_the_profiled_pass": round(secs_profiled * 1e3, 3),
+        "kernel_ms_sum_of_the_profiled_pass": round(sum(v["kernel_ms_total"] for v in kinds.values()), 3),
     }
 
 
-def run_collectives(torch, mw, dev, reps):
+COLL_N, COLL_WORLDS, COLL_S = 4, 8, 64 << 20
+
+
+def coll_alg_bytes(kind, n=COLL_N, S=COLL_S):
+    """Algorithmic bytes of one collective of one world (reads + writes), payload S per rank."""
+    return {"send/recv": 2 * 2 * S, "broadcast": n * S, "all-reduce": 2 * n * S, "reduce": (n + 1) * S,
+            "all-gather": n * S + n * n * S, "gather": 2 * n * S, "scatter": 2 * n * S}[kind]
+
+
+def run_collectives(torch, mw, dev, reps, timed=200, warm=20):
     """Large-payload bandwidth of every operation of the communicator: 8 worlds x 4 ranks, 64 MiB fp32 per
-    rank, all worlds outstanding together; kernel time from HIP events on the library's streams."""
-    n, nworlds, S = 4, 8, 64 << 20
+    rank drawn from the seeded N(0,1) pool, all worlds outstanding together; `warm` untimed and `timed` timed
+    launches per operation, kernel time from HIP events on the library's streams."""
+    from paper_2407_08980_amd.trace_runner import DevicePools
+    from workloads import HostPools
+    from workloads.data import POOL_ELEMS, rng_of
+
+    n, nworlds, S = COLL_N, COLL_WORLDS, COLL_S
     count = S // 4
     for w in range(nworlds):
         mw.mw_world_create(w, list(range(4 * w, 4 * w + 4)))
-    small = [[torch.zeros(S, dtype=torch.uint8, device=dev) for _ in range(n)] for _ in range(nworlds)]
-    big = [[torch.zeros(n * S, dtype=torch.uint8, device=dev) for _ in range(n)] for _ in range(nworlds)]
+    pools = DevicePools(HostPools(), dev)
+    rng = rng_of(20240708 + 6)
+
+    def drawn(nbytes):
+        t = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        pools.slice("f32", int(rng.integers(0, POOL_ELEMS)), nbytes, t)
+        return t
+
+    small = [[drawn(S) for _ in range(n)] for _ in range(nworlds)]
+    big = [[drawn(n * S) for _ in range(n)] for _ in range(nworlds)]
+    pristine = [[t.clone() for t in row] for row in small]  # sums are taken in place: inputs are put back every 16 launches
     torch.cuda.synchronize()
     NONE = mw.STREAM_NONE
     f32 = mw.MW_F32
@@ -764,40 +862,116 @@ def run_collectives(torch, mw, dev, reps):
                     out.append((mw.POST_SCATTER, w, r, 0, big[w][0].data_ptr() if r == 0 else None, count, f32, NONE, a))
         return out
 
-    # algorithmic bytes per collective (per world), kernel kind that runs it
-    table = {"send/recv": (2 * 2 * S, mw.KIND_COPY), "broadcast": (n * S, mw.KIND_BCAST),
-             "all-reduce": (2 * n * S, mw.KIND_REDUCE), "reduce": ((n + 1) * S, mw.KIND_REDUCE),
-             "all-gather": (n * S + n * n * S, mw.KIND_BCAST), "gather": (2 * n * S, mw.KIND_COPY),
-             "scatter": (2 * n * S, mw.KIND_COPY)}
-    res = {}
-    iters = max(3 * reps, 3)
-    for kind, (alg, kk) in table.items():
+    def restore():
+        for w in range(nworlds):
+            for r in range(n):
+                small[w][r].copy_(pristine[w][r])
+        torch.cuda.synchronize()
+
+    kernel_of = {"send/recv": mw.KIND_COPY, "broadcast": mw.KIND_BCAST, "all-reduce": mw.KIND_REDUCE,
+                 "reduce": mw.KIND_REDUCE, "all-gather": mw.KIND_BCAST, "gather": mw.KIND_COPY, "scatter": mw.KIND_COPY}
+    res, roofs = {}, {}
+    for kind, kk in kernel_of.items():
+        alg = coll_alg_bytes(kind)
         pb = mw.PostBatch(posts_of(kind))
-        for it in range(iters + 2):
-            if it == 2:
+        sums = kind in ("all-reduce", "reduce")
+        restore()
+        wall = 0.0
+        for it in range(warm + timed):
+            if it == warm:
                 mw.mw_profile_enable(True)
                 mw.mw_profile_read(kk)
-                torch.cuda.synchronize()
-                t0 = time.perf_counter()
+            if sums and it % 16 == 0 and it:
+                restore()  # keeps the running sums finite (outside the kernels' event brackets)
+            t0 = time.perf_counter()
             pb.post()
             mw.mw_flush()
             ps = mw.PollSet(list(pb.handles))
             while ps.poll():
                 pass
-        wall = time.perf_counter() - t0
+            if it >= warm:
+                wall += time.perf_counter() - t0
         launches, ms, _ = mw.mw_profile_read(kk)
         mw.mw_profile_enable(False)
-        res[kind] = {"kernel_ms": round(ms / launches, 4), "alg_traffic_GBps": round(nworlds * alg / (ms / launches) / 1e6, 1),
-                     "pct_of_hbm_peak": round(nworlds * alg / (ms / launches) / 1e6 / HBM_PEAK_GBPS * 100, 1),
-                     "end_to_end_GBps": round(iters * nworlds * alg / wall / 1e9, 1)}
+        roofs[kind] = roofline(KERNEL_NAME[kk], nworlds * alg * launches, launches, ms)
+        res[kind] = {"kernel": KERNEL_NAME[kk], "launches": launches, "kernel_ms": round(ms / launches, 4),
+                     "alg_traffic_GBps": roofs[kind]["achieved"], "pct_of_hbm_peak": round(roofs[kind]["frac"] * 100, 1),
+                     "end_to_end_GBps": round(timed * nworlds * alg / wall / 1e9, 1)}
+    restore()
     worst = min(v["alg_traffic_GBps"] for v in res.values())
+    roof = dict(roofs["all-reduce"])
+    roof["operation"] = "all-reduce (the reduction kernel; every operation's figure is in roofline_per_operation)"
     return {
-        "value": res["send/recv"]["end_to_end_GBps"] / 2, "ms_per_step": res["send/recv"]["kernel_ms"], "steps": iters,
+        "value": round(res["send/recv"]["end_to_end_GBps"] / 2, 1), "ms_per_step": res["send/recv"]["kernel_ms"], "steps": timed,
         "config": {"workload": "every operation of the communicator on large payloads: 8 worlds x 4 ranks, 64 MiB fp32 "
-                               "per rank, all worlds outstanding together", "worlds": nworlds, "ranks": n,
-                   "payload_dtype": "f32"},
-        "per_operation": res, "lowest_alg_traffic_GBps": worst, "roofline": None,
+                               "N(0,1) per rank, all worlds outstanding together; value = send/recv payload rate",
+                   "worlds": nworlds, "ranks": n, "payload_dtype": "f32", "warmup_launches": warm, "timed_launches": timed},
+        "per_operation": res, "lowest_alg_traffic_GBps": worst, "roofline": roof, "roofline_per_operation": roofs,
     }
+
+
+def cpu_baseline_collectives():
+    """The oracle's per-operation functions on ONE world of the collectives workload (4 ranks x 64 MiB fp32)."""
+    import numpy as np
+
+    import oracle
+    from workloads import HostPools
+    from workloads.data import POOL_ELEMS, pool_slice, rng_of
+
+    n, S = COLL_N, COLL_S
+    count = S // 4
+    pools = HostPools()
+    rng = rng_of(20240708 + 6)
+    x = [pool_slice(pools.get("f32"), "f32", int(rng.integers(0, POOL_ELEMS)), S) for _ in range(n)]
+    big = pool_slice(pools.get("f32"), "f32", int(rng.integers(0, POOL_ELEMS)), n * S)
+    dst = [np.empty(S, np.uint8) for _ in range(n)]
+    bigdst = [np.empty(n * S, np.uint8) for _ in range(n)]
+
+    def sendrecv():
+        for r in (0, 2):
+            dst[r + 1][:] = oracle.copy_result(x[r])
+
+    def bcast():
+        out = oracle.broadcast_result(x, 0)
+        for r in range(1, n):
+            dst[r][:] = out[r]
+
+    def allreduce():
+        s, _ = oracle.allreduce_sum_f64(x, count, "f32")
+        y = s.astype(np.float32).view(np.uint8)
+        for r in range(n):
+            dst[r][:] = y
+
+    def reduce_():
+        s, _ = oracle.reduce_result_f64(x, count, "f32")
+        dst[0][:] = s.astype(np.float32).view(np.uint8)
+
+    def allgather():
+        cat = oracle.all_gather_result(x)
+        for r in range(n):
+            bigdst[r][:] = cat
+
+    def gather():
+        bigdst[0][:] = oracle.gather_result(x)
+
+    def scatter():
+        for r in range(n):
+            dst[r][:] = oracle.scatter_result(big, n, r)
+
+    table = {"send/recv": sendrecv, "broadcast": bcast, "all-reduce": allreduce, "reduce": reduce_, "all-gather": allgather,
+             "gather": gather, "scatter": scatter}
+    per, total = {}, 0.0
+    for kind, fn in table.items():
+        t0 = time.perf_counter()
+        fn()
+        dt = time.perf_counter() - t0
+        total += dt
+        per[kind] = round(coll_alg_bytes(kind) / dt / 1e9, 2)
+    return {"value": round(per["send/recv"] / 2, 2), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "alg_traffic_GBps_per_operation": per,
+            "sample": f"each of the seven operations once on ONE of the 8 worlds (4 ranks x 64 MiB fp32), {total:.1f} s of "
+                      f"oracle time; value = send/recv payload rate, per-operation figures in algorithmic bytes per second "
+                      f"like the GPU's; host has {os.cpu_count()} logical CPUs"}
 
 
 def run_sweep(torch, mw, dev, reps):
@@ -849,6 +1023,14 @@ def run_sweep(torch, mw, dev, reps):
 
             pbm, pbs = batch(True), batch(False)
             run(pbm), run(pbs)
+            if count == sizes[-1] and senders == 3:  # kernel time of the largest case, in a pass of its own
+                mw.mw_profile_enable(True)
+                mw.mw_profile_read(mw.KIND_COPY)
+                run(pbm)
+                launches, kernel_ms, op_bytes = mw.mw_profile_read(mw.KIND_COPY)
+                mw.mw_profile_enable(False)
+                roof = roofline("mw_k_copy", 2 * op_bytes, launches, kernel_ms,
+                                note="4 MB x 3 senders, one world per sender: one launch moves a window of 48 messages")
             tm, ts = [], []
             for _ in range(max(reps, 1) * 10):  # one run lasts 1-10 ms
                 ts.append(run(pbs))
@@ -871,7 +1053,7 @@ def run_sweep(torch, mw, dev, reps):
         "config": {"workload": "paper-shaped sweep: 1-3 senders -> 1 receiver, fp32 tensors of 4 KB / 40 KB / 400 KB / 4 MB, "
                                "single world vs one world per sender, 128 windows of 16 messages per sender",
                    "payload_dtype": "f32"},
-        "sweep": out, "worst_loss_pct": round(worst, 2), "roofline": None,
+        "sweep": out, "worst_loss_pct": round(worst, 2), "roofline": roof,
     }
 
 
@@ -918,6 +1100,13 @@ def run_online(torch, mw, dev, reps):
     one = batch([1])
     run(one, 10, (0, 1))
     points = []
+    mw.mw_profile_enable(True)  # kernel time while W1 streams alone, in a pass of its own
+    mw.mw_profile_read(mw.KIND_COPY)
+    run(one, 20, (0, 1))
+    launches, kernel_ms, op_bytes = mw.mw_profile_read(mw.KIND_COPY)
+    mw.mw_profile_enable(False)
+    roof = roofline("mw_k_copy", 2 * op_bytes, launches, kernel_ms,
+                    note="W1 alone: one launch moves a window of 50 tensors of 4 MB")
     for _ in range(3):  # W1 alone
         t = run(one, nb, (0, 1))
         points.append({"phase": "W1 only", "W1_GBps": round(per_point * count * 4 / t / 1e9, 1)})
@@ -963,7 +1152,7 @@ def run_online(torch, mw, dev, reps):
         "points": points,
         "world_create_latency_us": {"first_join_while_streaming": round(first_join * 1e6, 1),
                                     "median": round(joins[len(joins) // 2] * 1e6, 1), "max": round(joins[-1] * 1e6, 1)},
-        "w1_still_in_flight_at_join": bool(still_running), "roofline": None,
+        "w1_still_in_flight_at_join": bool(still_running), "roofline": roof,
     }
 
 
@@ -995,7 +1184,7 @@ def main():
     elif args.workload == "config1":
         res = run_config1(torch, mw, dev, args.reps)
     elif args.workload == "collectives":
-        res = run_collectives(torch, mw, dev, args.reps)
+        res = run_collectives(torch, mw, dev, args.reps, args.coll_launches, args.coll_warmup)
     elif args.workload == "sweep":
         res = run_sweep(torch, mw, dev, args.reps)
     elif args.workload == "online":
@@ -1003,11 +1192,75 @@ def main():
     else:
         res = run_config5(torch, mw, dev, args.ops, args.reps, args.window, args.depth)
     mw.mw_shutdown()
+    torch.cuda.empty_cache()
     out = {"metric": METRIC, "value": res.pop("value"), "unit": "GB/s", "n_gpus": 1, "steps": res.pop("steps"),
            "warmup": args.warmup, "ms_per_step": res.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "f32" if args.workload == "config3" else "u8", "data": "synthetic"}
     out.update(res)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_of(args)
     print(json.dumps(out))
+
+
+def cpu_baseline_config4(steps, abort_step):
+    """The oracle on a bounded sample of the fan-in workload: its first 5 steps, the 4 steps around the abort and
+    its last 5 steps, all 16 worlds, one thread."""
+    import numpy as np
+
+    from oracle import BF16, DONE, WorldOracle
+    from workloads import HostPools
+    from workloads.data import POOL_ELEMS, pool_slice, rng_of
+
+    n, count = 16, 8 * 2048 * 5120
+    nbytes = count * 2
+    pools = HostPools()
+    rng = rng_of(20240708 + 4)
+    src = [pool_slice(pools.get("bf16"), "bf16", int(rng.integers(0, POOL_ELEMS)), nbytes) for _ in range(n)]
+    dst = [np.full(nbytes, 0xA5, dtype=np.uint8) for _ in range(n)]
+    sample = sorted(set(range(0, min(5, steps))) | {s for s in range(abort_step - 2, abort_step + 2) if 0 <= s < steps}
+                    | set(range(max(0, steps - 5), steps)))
+    orc = WorldOracle(n + 1)
+    for w in range(n):
+        orc.create(w, (w, n))
+    aborted = False
+    t0 = time.perf_counter()
+    for s in sample:
+        if s >= abort_step and not aborted:
+            orc.abort_worker(7)
+            aborted = True
+        for w in range(n):
+            orc.post_send(w, 0, 1, src[w], count, BF16)
+            orc.post_recv(w, 0, 1, dst[w], count, BF16)
+    dt = time.perf_counter() - t0
+    done = sum(1 for st in orc.result if st == DONE) // 2
+    return {"value": round(done * nbytes / dt / 1e9, 2), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"steps {sample} of the same workload (first 5, around the abort, last 5), all 16 worlds: {done} messages of "
+                      f"{nbytes >> 20} MiB delivered, {2 * len(sample) * n - 2 * done} posts refused, {dt:.1f} s of oracle time; host "
+                      f"has {os.cpu_count()} logical CPUs"}
+
+
+def cpu_baseline_of(args):
+    """The CPU oracle on a bounded sample of the workload that was just measured (one thread)."""
+    import workloads
+
+    w = args.workload
+    if w == "config4":
+        return cpu_baseline_config4(args.steps if args.steps != 50 else 300, args.abort_step)
+    if w == "collectives":
+        return cpu_baseline_collectives()
+    if w == "config1":
+        return oracle_on_trace(workloads.config1(), "the whole workload: 200 messages of 32 KiB through 2 worlds, then a broadcast "
+                                                    "and an all-reduce per world")
+    if w == "config3":
+        return oracle_on_trace(workloads.config3(iters=100, check_iters=()), "the first 100 of the 500 iterations, all 4 worlds")
+    if w == "config5":
+        return oracle_on_trace(workloads.config5(n_ops=400), "the same recipe at 400 operations instead of 10 000 (64 worlds, "
+                                                             "same size and kind mix, 3 worker aborts)")
+    if w == "sweep":
+        return oracle_on_trace(workloads.multi_sender(3, 1_000_000, True, window=16, n_windows=4),
+                               "the largest case: 3 senders x 4 MB, one world per sender, 4 windows of 16 messages per sender")
+    return oracle_on_trace(workloads.online_recovery(), "the online-instantiation and recovery scenario at 4 MB per tensor: 5 "
+                                                        "workers, 6 worlds, one worker failing, windows of 4 per world")
 
 
 if __name__ == "__main__":

@@ -76,7 +76,7 @@ struct CopyArgs {
   uint32_t n;
   uint32_t chunk_shift;
   uint32_t first_chunk[kCopyMax + 1];  // first_chunk[i] = chunks before entry i; [n] = total
-  uint32_t pad;
+  uint32_t rotate;  // see chunk_of_workgroup
   CopyEnt e[kCopyMax];
 };
 static_assert(sizeof(CopyArgs) <= 4096, "kernel argument block");
@@ -91,7 +91,7 @@ struct CollEnt {
 };
 struct CollArgs {
   uint32_t n;
-  uint32_t pad0;
+  uint32_t rotate;  // see chunk_of_workgroup
   uint32_t first_chunk[kCollMax + 1];
   uint32_t pad;
   CollEnt e[kCollMax];
@@ -101,6 +101,22 @@ static_assert(sizeof(CollArgs) <= 4096, "kernel argument block");
 // ------------------------------------------------------------------------------------------------
 // device helpers
 // ------------------------------------------------------------------------------------------------
+
+// Workgroup -> chunk.  The hardware deals consecutive workgroups out to the 8 XCDs in turn, so with chunk = workgroup
+// index XCD k would only ever touch addresses congruent to k x chunk modulo 8 x chunk: a fixed eighth of the address
+// bits that select L2 and memory channels.  Rotating every full row of 8 workgroups by its row number lets each XCD
+// sweep all residues.  Kernel time, 8 worlds, mean over 7-8 relative placements of the buffers (offsets of 0 B ... 2 MiB
+// between consecutive buffers; a placement alone moves a figure by +-3 %), TB/s of algorithmic traffic:
+//   copy, 64 KiB chunks        5.88 -> 6.32  (128 KiB chunks without rotation: 6.26)
+//   broadcast, 4 ranks, 64 KiB  5.60 -> 6.14  (128 KiB without: 5.94)
+//   reduce to a root, 4 ranks   6.15 (32 KiB) -> 6.35 (24 KiB)
+//   all-reduce, 4 ranks, 12 KiB 6.09 (5.86-6.33 by placement) -> 6.03 (5.96-6.12): evens the placements out, gains nothing
+// so copies, fan-outs and reductions to a root rotate, launches holding an all-reduce do not.  Adding further row bits
+// to the rotation, or xor-ing instead, changed nothing.  The last, partial row keeps the identity: the map stays one to one.
+__device__ __forceinline__ uint32_t chunk_of_workgroup(uint32_t b, uint32_t grid, uint32_t rotate) {
+  if (!rotate || b >= (grid & ~7u)) return b;
+  return (b & ~7u) | ((b + (b >> 3)) & 7u);
+}
 
 // Index of the operation that owns chunk c: the largest i with first_chunk[i] <= c.
 __device__ __forceinline__ int find_op(const uint32_t* first_chunk, int n, uint32_t c) {
@@ -261,7 +277,7 @@ __device__ __forceinline__ void move_any(uint64_t align, rsrc_t s, const rsrc_t*
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kCopyWG) void mw_k_copy(const CopyArgs a, RingSlot* __restrict__ slots,
                                                       uint32_t* __restrict__ host_flags) {
-  const uint32_t c = blockIdx.x;
+  const uint32_t c = chunk_of_workgroup(blockIdx.x, gridDim.x, a.rotate);
   const int op = find_op(a.first_chunk, (int)a.n, c);
   const uint64_t src = a.e[op].src, dst = a.e[op].dst, nbytes = a.e[op].nbytes;
   const uint32_t slot = a.e[op].slot, gen = a.e[op].gen;
@@ -294,7 +310,7 @@ __global__ __launch_bounds__(kCopyWG) void mw_k_copy(const CopyArgs a, RingSlot*
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kCopyWG) void mw_k_bcast(const CollArgs a, RingSlot* __restrict__ slots,
                                                        uint32_t* __restrict__ host_flags) {
-  const uint32_t c = blockIdx.x;
+  const uint32_t c = chunk_of_workgroup(blockIdx.x, gridDim.x, a.rotate);
   const int op = find_op(a.first_chunk, (int)a.n, c);
   const uint64_t nbytes = a.e[op].nbytes;
   const uint32_t slot = a.e[op].slot, gen = a.e[op].gen, nbuf = a.e[op].nbuf;
@@ -512,7 +528,7 @@ template <bool LDS>
 __global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs a, RingSlot* __restrict__ slots,
                                                           uint32_t* __restrict__ host_flags) {
   extern __shared__ u32x4 tile[];  // LDS-staged variant: ranks x stride vectors, sized by the launch
-  const uint32_t c = blockIdx.x;
+  const uint32_t c = chunk_of_workgroup(blockIdx.x, gridDim.x, a.rotate);
   const int op = find_op(a.first_chunk, (int)a.n, c);
   const uint64_t nbytes = a.e[op].nbytes;
   const uint32_t slot = a.e[op].slot, gen = a.e[op].gen, nbuf = a.e[op].nbuf;
@@ -861,16 +877,20 @@ class HipDevice : public Device {
 
   // Chunk size of an entry with `nbuf` buffers in a launch of `total_bytes`: enough workgroups to fill
   // 256 CUs several times over, chunks large enough to amortise the per-chunk completion protocol.
-  // Copies and fan-outs peak at 128 KiB chunks (two passes of 1024 threads x 4 x 16 B): measured 6.44 TB/s
-  // of traffic on 8 x 512 MiB against 6.01 (64 KiB) and 6.34 (256 KiB).
-  // All-reduce peaks where a workgroup's chunks of all ranks together come to 40-64 KiB, whatever the number
-  // of ranks (TB/s of traffic on 8 worlds x 256 MiB, by chunk per rank):
+  // With the workgroup -> chunk rotation (chunk_of_workgroup) the kernels peak where one workgroup reads about
+  // 64 KiB in one burst (TB/s of algorithmic traffic, 8 worlds, kernel time, by chunk):
+  //   copy 8 x 512 MiB        32 KiB 5.37, 48 KiB 5.87, 64 KiB 6.49, 80 KiB 6.12, 96 KiB 6.03, 128 KiB 6.32, 256 KiB 6.20
+  //   broadcast, 4 ranks      32 KiB 5.61, 48 KiB 5.78, 64 KiB 6.25, 80 KiB 6.06, 96 KiB 5.83, 128 KiB 6.10
+  //   broadcast, 64 KiB / 128 KiB:   2 ranks 6.44 / 6.33   3 ranks 6.40 / 6.21   5 ranks 6.10 / 5.99   8 ranks 5.91 / 5.80
+  // All-reduce (not rotated) peaks where a workgroup's chunks of all ranks together come to 40-64 KiB, whatever the
+  // number of ranks (by chunk per rank):
   //   2 ranks 3.1 (8 KiB) 5.3 (16) 6.2 (24) 6.1 (32)     3 ranks 4.4 (8) 6.0 (16) 5.9 (32)
   //   4 ranks 5.4 (8) 6.2 (12) 5.9 (16) 5.5 (32)          5 ranks 6.1 (8) 6.0 (12) 5.7 (16)
   //   6 ranks 6.5 (8) 5.6 (16)    7 ranks 6.4 (8) 5.3 (16)    8 ranks 5.1 (4) 5.9 (8) 5.1 (16)
-  // A reduce to one root writes one buffer only and peaks at larger chunks (8 / 16 / 32 / 64 KiB):
-  //   2 ranks 2.4 / 4.3 / 6.2 / 6.0    4 ranks 3.6 / 5.8 / 6.3 / 5.6    5 ranks 4.2 / 6.1 / 6.1 / 5.6
-  //   6 ranks 4.6 / 6.3 / 6.0 / 5.5    8 ranks 5.2 / 6.1 / 5.7 / 5.5
+  // A reduce to one root writes one buffer only and peaks where the ranks' chunks come to about 96 KiB:
+  //   2 ranks 5.55 (24 KiB) 6.25 (32) 6.37 (48) 6.32 (64)    3 ranks 6.25 (24 KiB) 6.47 (32) 6.24 (48)
+  //   4 ranks 5.59 (16 KiB) 6.43 (24) 6.17 (32)               5 ranks 6.05 (16 KiB) 6.31 (24) 6.06 (32)
+  //   6 ranks 5.69 (12 KiB) 6.21 (16) 6.21 (24) 5.92 (32)     8 ranks 5.19 (8 KiB) 6.17 (12) 5.68 (16) 6.02 (24)
   uint32_t pick_chunk_bytes(uint32_t kind, uint64_t total_bytes, uint32_t nbuf, bool all_ranks_written) const {
     if (cfg_.chunk_bytes) return cfg_.chunk_bytes;
     // Smaller launches take smaller chunks, down to where the launch still has ~512 (copies, fan-outs) or
@@ -881,10 +901,11 @@ class HipDevice : public Device {
     //   all-reduce, 2 x 2 MiB        8 KiB  7.7 us, 16 KiB  8.3, 32 KiB  9.1
     const uint64_t groups = kind == kReduce ? 256 : 512;
     const uint32_t fill = 1u << std::min(30u, floor_log2(total_bytes / groups + 1));
-    if (kind != kReduce) return std::min(128u << 10, std::max(16u << 10, fill));
-    const uint32_t best = !all_ranks_written ? (nbuf <= 5 ? 32u << 10 : 16u << 10)
-                          : nbuf <= 2 ? 32u << 10 : nbuf == 3 ? 16u << 10 : nbuf == 4 ? 12u << 10 : 8u << 10;
-    return std::min(best, std::max(8u << 10, fill));
+    if (kind != kReduce) return std::min(64u << 10, std::max(16u << 10, fill));
+    static const uint32_t all_kib[kMaxBufs + 1] = {32, 32, 32, 16, 12, 8, 8, 8, 8};
+    static const uint32_t root_kib[kMaxBufs + 1] = {48, 48, 48, 32, 24, 24, 16, 16, 12};
+    const uint32_t best = (all_ranks_written ? all_kib : root_kib)[std::min<uint32_t>(nbuf, kMaxBufs)] << 10;
+    return std::min(best, std::max(std::min(best, 8u << 10), fill));
   }
 
   struct Ent {  // one kernel entry of an operation
@@ -1062,6 +1083,7 @@ class HipDevice : public Device {
       CopyArgs& a = copy_args_;
       a.n = (uint32_t)n;
       a.chunk_shift = floor_log2(launch_chunk);
+      a.rotate = 1;
       for (int i = 0; i < n; ++i) {
         const Ent& e = ents_[(size_t)i];
         a.first_chunk[i] = at;
@@ -1074,6 +1096,8 @@ class HipDevice : public Device {
     } else {
       CollArgs& a = coll_args_;
       a.n = (uint32_t)n;
+      a.rotate = 1;
+      for (const Ent& e : ents_) a.rotate &= kind == kBcast || (e.flags >> 24) != (1u << e.nbuf) - 1u;
       for (int i = 0; i < n; ++i) {
         const Ent& e = ents_[(size_t)i];
         a.first_chunk[i] = at;

@@ -519,11 +519,12 @@ def test_ring_journal_header_and_isolation_across_abort(torch, mw):
 
 @pytest.mark.parametrize("n", [2, 3, 4, 5, 6, 8])
 def test_large_reductions_in_every_chunk_size_the_library_chooses(torch, mw, n):
-    """The chunk of a reduce entry depends on the number of ranks and on who is written (all-reduce 32 / 16 /
-    12 / 8 KiB, reduce to a root 32 / 16 KiB; two vectors per thread for 2 ranks).  Payloads here are large
-    enough for the largest choice, with a ragged tail; the journal in the world's ring tells which was taken."""
+    """The chunk of a reduce entry depends on the number of ranks and on who is written (all-reduce 32 ... 8 KiB,
+    reduce to a root 48 ... 12 KiB, sizes that are not powers of two among them; two vectors per thread for 2
+    ranks).  Payloads here are large enough for the largest choice, with a ragged tail; the journal in the world's
+    ring tells which was taken."""
     mw.mw_world_create(0, list(range(n)))
-    count = (9 << 20) // 4 + 1237  # 9 MiB and a tail per rank: several hundred chunks of any size
+    count = (17 << 20) // 4 + 1237  # 17 MiB and a tail per rank: several hundred chunks of any size
     rng = np.random.default_rng(900 + n)
     seen = set()
     for dtype, root in (("f32", None), ("bf16", None), ("f32", n - 1)):
@@ -556,7 +557,7 @@ def test_large_reductions_in_every_chunk_size_the_library_chooses(torch, mw, n):
         assert last["nchunks"] * last["chunk"] >= host[0].size > (last["nchunks"] - 1) * last["chunk"]
         seen.add((root is None, last["chunk"]))
     want_all = {2: 32, 3: 16, 4: 12}.get(n, 8) << 10
-    want_root = (32 if n <= 5 else 16) << 10
+    want_root = {2: 48, 3: 32, 4: 24, 5: 24, 6: 16, 8: 12}[n] << 10
     assert seen == {(True, want_all), (False, want_root)}, seen
 
 
