@@ -420,7 +420,7 @@ def run_config4(torch, mw, dev, steps, abort_step, reps):
             pb = pbs[s % 4]
             pb.post(check=False)
             mw.mw_flush()
-            cur = mw.PollSet([h for h in pb.handles if h])
+            cur = pb.pollset()
             if prev is not None:
                 _poll_until_idle_set(prev)
                 stamps.append(time.perf_counter() - t0)
@@ -517,7 +517,7 @@ def run_config3(torch, mw, dev, iters, reps, lds):
             pb = pbs[it % POOL_K]
             pb.post()
             mw.mw_flush()
-            cur = mw.PollSet(list(pb.handles))
+            cur = pb.pollset()
             if prev is not None:
                 while prev.poll():
                     pass
@@ -595,7 +595,7 @@ def run_config1(torch, mw, dev, reps):
         for pb in pbs:
             pb.post()
             mw.mw_flush()
-            ps = mw.PollSet(list(pb.handles))
+            ps = pb.pollset()
             while ps.poll():
                 pass
         return time.perf_counter() - t0
@@ -651,6 +651,8 @@ def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
     p2p / broadcast / all-reduce, 4 KiB - 64 MiB, fp32/bf16, three worker aborts), <= 64 outstanding (`depth`
     windows of `window` operations in flight).
     Buffers are slices of one pre-filled slab so that no initialisation runs inside the timed region."""
+    import gc
+
     import workloads
 
     assert window * depth <= 64
@@ -717,6 +719,7 @@ def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
                 if op.kind == "create":
                     mw.mw_world_create(world_base + op.world, list(op.members))
         segs = segments(world_base, p2p_only, single)
+        gc.collect()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         live, prev = [], []
@@ -728,7 +731,7 @@ def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
                 mw.mw_worker_abort(x)
             else:  # end of a window: launch it, then wait until fewer than `depth` are in flight
                 mw.mw_flush()
-                prev.append([mw.PollSet([h for h in pb.handles if h]) for pb in live])
+                prev.append([pb.pollset() for pb in live])
                 live = []
                 while len(prev) >= depth:
                     drain(prev.pop(0))
@@ -789,7 +792,7 @@ def run_config5(torch, mw, dev, n_ops, reps, window=32, depth=2):
         "config": {"workload": f"config 5: mixed scale-out, 64 worlds of 2-4 over 32 workers, {n_ops} operations 70/20/10 % "
                                "send-recv / broadcast / all-reduce, 4 KiB - 64 MiB log-uniform, fp32/bf16, 3 worker "
                                f"aborts, {depth} windows of {window} operations in flight", "worlds": 64, "payload_dtype": "f32/bf16"},
-        "payload_bytes_done": payload, "algorithmic_bytes": alg,
+        "payload_bytes_done": payload, "algorithmic_bytes": alg, "pass_ms": [round(x * 1e3, 3) for x in times],
         "hbm_traffic_GBps": round(alg / secs / 1e9, 1), "pct_of_hbm_peak": round(alg / secs / 1e9 / HBM_PEAK_GBPS * 100, 2),
         "p2p_subset_single_world_GBps": round(p2p_payload / (sum(sw_t) / len(sw_t)) / 1e9, 1) if reps else None,
         "p2p_subset_multi_world_GBps": round(p2p_payload / (sum(mw_t) / len(mw_t)) / 1e9, 1) if reps else None,
@@ -886,7 +889,7 @@ def run_collectives(torch, mw, dev, reps, timed=200, warm=20):
             t0 = time.perf_counter()
             pb.post()
             mw.mw_flush()
-            ps = mw.PollSet(list(pb.handles))
+            ps = pb.pollset()
             while ps.poll():
                 pass
             if it >= warm:
@@ -1005,14 +1008,15 @@ def run_sweep(torch, mw, dev, reps):
                         posts.append((mw.POST_SEND, w, a, 0, src[k][j].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE))
                 return mw.PostBatch(posts)
 
-            def run(pb):
+            def run(pair):
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
                 prev = None
-                for _ in range(n_windows):
+                for i in range(n_windows):
+                    pb = pair[i % 2]  # two windows are in flight: each needs its own handle array
                     pb.post()
                     mw.mw_flush()
-                    cur = mw.PollSet(list(pb.handles))
+                    cur = pb.pollset()
                     if prev is not None:
                         while prev.poll():
                             pass
@@ -1021,7 +1025,7 @@ def run_sweep(torch, mw, dev, reps):
                     pass
                 return time.perf_counter() - t0
 
-            pbm, pbs = batch(True), batch(False)
+            pbm, pbs = (batch(True), batch(True)), (batch(False), batch(False))
             run(pbm), run(pbs)
             if count == sizes[-1] and senders == 3:  # kernel time of the largest case, in a pass of its own
                 mw.mw_profile_enable(True)
@@ -1077,16 +1081,17 @@ def run_online(torch, mw, dev, reps):
                 posts.append((mw.POST_SEND, w, 1, 0, src[k][j].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE))
         return mw.PostBatch(posts)
 
-    def run(pb, n_batches, beat):
+    def run(pair, n_batches, beat):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         prev = None
-        for _ in range(n_batches):
+        for i in range(n_batches):
             for k in beat:
                 mw.mw_heartbeat(k)
+            pb = pair[i % 2]  # two windows are in flight: each needs its own handle array
             pb.post(check=False)
             mw.mw_flush()
-            cur = mw.PollSet([h for h in pb.handles if h])
+            cur = pb.pollset()
             if prev is not None and prev.n:
                 while prev.poll():
                     pass
@@ -1097,18 +1102,19 @@ def run_online(torch, mw, dev, reps):
         return time.perf_counter() - t0
 
     nb = per_point // window
-    one = batch([1])
-    run(one, 10, (0, 1))
+    one_pair = (batch([1]), batch([1]))
+    one = one_pair[0]
+    run(one_pair, 10, (0, 1))
     points = []
     mw.mw_profile_enable(True)  # kernel time while W1 streams alone, in a pass of its own
     mw.mw_profile_read(mw.KIND_COPY)
-    run(one, 20, (0, 1))
+    run(one_pair, 20, (0, 1))
     launches, kernel_ms, op_bytes = mw.mw_profile_read(mw.KIND_COPY)
     mw.mw_profile_enable(False)
     roof = roofline("mw_k_copy", 2 * op_bytes, launches, kernel_ms,
                     note="W1 alone: one launch moves a window of 50 tensors of 4 MB")
     for _ in range(3):  # W1 alone
-        t = run(one, nb, (0, 1))
+        t = run(one_pair, nb, (0, 1))
         points.append({"phase": "W1 only", "W1_GBps": round(per_point * count * 4 / t / 1e9, 1)})
     # join: create W2 while W1's last windows are still in flight
     one.post()
@@ -1130,7 +1136,7 @@ def run_online(torch, mw, dev, reps):
         joins.append(time.perf_counter() - t0)
         while inflight.poll():
             pass
-    two = batch([1, 2])
+    two = (batch([1, 2]), batch([1, 2]))
     for _ in range(3):  # both worlds
         t = run(two, nb, (0, 1, 2))
         g = round(per_point * count * 4 / t / 1e9, 1)
@@ -1169,6 +1175,9 @@ def main():
         sys.exit(2)
     from paper_2407_08980_amd import binding as mw
 
+    import gc
+
+    gc.disable()  # a generation-2 collection inside a timed pass costs tens of milliseconds (seen: 50 ms in a 26 ms pass)
     mw.lib()
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)

@@ -267,6 +267,16 @@ class PostBatch:
             _ck(rc, "mw_post_many")
         return rc
 
+    def pollset(self):
+        """A PollSet over this batch's own handle array (no copy): it always polls the handles of the latest post().
+        Refused posts have handle 0, which polls as MW_EBADHANDLE, i.e. not pending."""
+        ps = self.__dict__.get("_pollset")
+        if ps is None:
+            ps = PollSet.__new__(PollSet)
+            ps.n, ps.handles, ps.states = self.n, self.handles, (C.c_int * self.n)()
+            self._pollset = ps
+        return ps
+
 
 def mw_post_many(posts):
     """Post a list of (kind, world, a, b, buf, count, dtype, stream); returns (handles, results)."""

@@ -50,8 +50,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kCopyWG = 1024;    // threads per workgroup, copy / broadcast
 constexpr int kCopyU = 4;        // 16-byte vectors in flight per thread
 constexpr int kReduceWG = 1024;  // threads per workgroup, (all-)reduce
-constexpr int kCopyMax = 72;     // entries per copy launch (kernel arguments stay under 4 KiB)
-constexpr int kCollMax = 36;     // entries per fan-out / reduce launch
+constexpr int kCopyMax = 64;     // entries per copy launch (kernel arguments stay under 4 KiB)
+constexpr int kCollMax = 35;     // entries per fan-out / reduce launch
 // (All-)reduce, register path: 16-byte vectors per rank in flight per thread, by number of ranks.  Two ranks
 // give a thread only two loads per vector; a second vector brings it to the four that the other counts have.
 constexpr int reduce_u(int n) { return n == 2 ? 2 : 1; }
@@ -71,15 +71,21 @@ struct CopyEnt {
   uint32_t slot, gen;
   uint32_t world_id, world_epoch;  // journalled only
   uint32_t op_chunks, flags;
+  uint32_t target, pad;  // the arrival count at which the operation is complete (see retire_chunk)
 };
+// The argument block travels by value in the kernel-argument segment, which the host fills through the PCIe
+// aperture at launch: 4 KiB of it cost 1.5 us of host time per launch, so every kernel exists for three capacities
+// and a launch takes the smallest that holds its entries.
+template <int CAP>
 struct CopyArgs {
   uint32_t n;
   uint32_t chunk_shift;
-  uint32_t first_chunk[kCopyMax + 1];  // first_chunk[i] = chunks before entry i; [n] = total
+  uint32_t first_chunk[CAP + 1];  // first_chunk[i] = chunks before entry i; [n] = total
   uint32_t rotate;  // see chunk_of_workgroup
-  CopyEnt e[kCopyMax];
+  CopyEnt e[CAP];
 };
-static_assert(sizeof(CopyArgs) <= 4096, "kernel argument block");
+constexpr int kCopyCap[3] = {8, 24, kCopyMax};
+static_assert(sizeof(CopyArgs<kCopyMax>) <= 4096, "kernel argument block");
 
 struct CollEnt {
   uint64_t buf[kMaxBufs];
@@ -88,15 +94,18 @@ struct CollEnt {
   uint32_t chunk_bytes;  // per entry: the best chunk of a reduce entry depends on its number of ranks
   uint32_t world_id, world_epoch;  // journalled only
   uint32_t op_chunks, flags;
+  uint32_t target, pad;
 };
+template <int CAP>
 struct CollArgs {
   uint32_t n;
   uint32_t rotate;  // see chunk_of_workgroup
-  uint32_t first_chunk[kCollMax + 1];
+  uint32_t first_chunk[CAP + 1];
   uint32_t pad;
-  CollEnt e[kCollMax];
+  CollEnt e[CAP];
 };
-static_assert(sizeof(CollArgs) <= 4096, "kernel argument block");
+constexpr int kCollCap[3] = {4, 12, kCollMax};
+static_assert(sizeof(CollArgs<kCollMax>) <= 4096, "kernel argument block");
 
 // ------------------------------------------------------------------------------------------------
 // device helpers
@@ -199,22 +208,23 @@ struct Io<unsigned char> {
 
 // Completion protocol.  Every wave waits until its own write-through stores are acknowledged,
 // the workgroup meets, then one thread counts the chunk in (device-scope atomic, performed at
-// the L2 / memory side).  The workgroup that brings the count to nchunks knows that every other
-// chunk's stores were acknowledged before their count-in; it re-arms the counter and publishes
-// the operation's generation in the ring slot (HBM) and in the host-pinned word the host polls.
+// the memory side).  A slot's arrival counter only ever counts up: the host keeps the running total
+// of chunks it has sent through the slot and hands every operation the count at which it is complete
+// (`target`), so nothing has to be re-armed -- there is no store that a later operation in the same
+// slot could overtake.  The workgroup that brings the count to `target` knows that every other chunk's
+// stores were acknowledged before their count-in; it publishes the operation's generation in the ring
+// slot (HBM, the journal) and in the host-pinned word the host polls.  An operation of a single chunk
+// is complete when that chunk is: it skips the counter (and one memory round trip).
 __device__ __forceinline__ void retire_chunk(RingSlot* slots, uint32_t* host_flags, uint32_t slot, uint32_t gen,
-                                             uint32_t nchunks) {
+                                             uint32_t nchunks, uint32_t target) {
   __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): all of this wave's stores are performed
   __syncthreads();
   if (threadIdx.x == 0) {
     SlotSync* s = &slots[slot].s;
-    uint32_t prev = __hip_atomic_fetch_add(&s->arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (prev + 1 == nchunks) {
-      __hip_atomic_store(&s->arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    bool last = nchunks == 1;
+    if (!last) last = __hip_atomic_fetch_add(&s->arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 == target;
+    if (last) {
       __hip_atomic_store(&s->done_gen, gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      // The host may recycle the slot as soon as it sees the flag: the re-arm and the generation must
-      // have been performed before the flag store is issued.  One thread per operation: costs nothing.
-      __builtin_amdgcn_s_waitcnt(0);
       __hip_atomic_store(&host_flags[slot], gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
   }
@@ -275,7 +285,8 @@ __device__ __forceinline__ void move_any(uint64_t align, rsrc_t s, const rsrc_t*
 // ------------------------------------------------------------------------------------------------
 // K1: batched multi-world copy
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kCopyWG) void mw_k_copy(const CopyArgs a, RingSlot* __restrict__ slots,
+template <int CAP>
+__global__ __launch_bounds__(kCopyWG) void mw_k_copy(const CopyArgs<CAP> a, RingSlot* __restrict__ slots,
                                                       uint32_t* __restrict__ host_flags) {
   const uint32_t c = chunk_of_workgroup(blockIdx.x, gridDim.x, a.rotate);
   const int op = find_op(a.first_chunk, (int)a.n, c);
@@ -302,13 +313,14 @@ __global__ __launch_bounds__(kCopyWG) void mw_k_copy(const CopyArgs a, RingSlot*
   }
   const rsrc_t dw[1] = {window(dst + off, len)};
   move_any<kCopyWG, kCopyU, 1>(src | dst, window(src + off, len), dw, 1, (uint32_t)len);
-  retire_chunk(slots, host_flags, slot, gen, nchunks);
+  retire_chunk(slots, host_flags, slot, gen, nchunks, a.e[op].target);
 }
 
 // ------------------------------------------------------------------------------------------------
 // K2: broadcast fan-out
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kCopyWG) void mw_k_bcast(const CollArgs a, RingSlot* __restrict__ slots,
+template <int CAP>
+__global__ __launch_bounds__(kCopyWG) void mw_k_bcast(const CollArgs<CAP> a, RingSlot* __restrict__ slots,
                                                        uint32_t* __restrict__ host_flags) {
   const uint32_t c = chunk_of_workgroup(blockIdx.x, gridDim.x, a.rotate);
   const int op = find_op(a.first_chunk, (int)a.n, c);
@@ -342,7 +354,7 @@ __global__ __launch_bounds__(kCopyWG) void mw_k_bcast(const CollArgs a, RingSlot
     d->chunk_bytes = (uint32_t)chunk;
   }
   move_any<kCopyWG, kCopyU, kMaxBufs - 1>(align, window(a.e[op].buf[0] + off, len), dw, (int)nbuf - 1, (uint32_t)len);
-  retire_chunk(slots, host_flags, slot, gen, nchunks);
+  retire_chunk(slots, host_flags, slot, gen, nchunks, a.e[op].target);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -524,8 +536,8 @@ __device__ __forceinline__ void reduce_scalar(const rsrc_t* w, int nbuf, uint32_
   }
 }
 
-template <bool LDS>
-__global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs a, RingSlot* __restrict__ slots,
+template <bool LDS, int CAP>
+__global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs<CAP> a, RingSlot* __restrict__ slots,
                                                           uint32_t* __restrict__ host_flags) {
   extern __shared__ u32x4 tile[];  // LDS-staged variant: ranks x stride vectors, sized by the launch
   const uint32_t c = chunk_of_workgroup(blockIdx.x, gridDim.x, a.rotate);
@@ -580,7 +592,7 @@ __global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs a, RingS
     if (bf16) reduce_scalar<true>(w, (int)nbuf, wmask, first, nelem);
     else reduce_scalar<false>(w, (int)nbuf, wmask, first, nelem);
   }
-  retire_chunk(slots, host_flags, slot, gen, nchunks);
+  retire_chunk(slots, host_flags, slot, gen, nchunks, a.e[op].target);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -625,6 +637,7 @@ class HipDevice : public Device {
     launched_ = launched;
     cur_slots_ = slots_;
     cur_flags_ = flags_dev_;
+    counts_ = arena_counts_.data();
     host_flags_ok_ = true;
     if (chk(hipSetDevice(dev_))) return MW_EHIP;
     // Which caller streams still have work pending?  One query per distinct stream.  A stream with nothing
@@ -705,6 +718,8 @@ class HipDevice : public Device {
     launched_ = static_launched_.data();
     cur_slots_ = sslots;
     cur_flags_ = sflags;
+    std::memset(static_counts_, 0, sizeof(static_counts_));  // the fill kernel above zeroes the device counters
+    counts_ = static_counts_;
     host_flags_ok_ = false;
     group_of_.assign((size_t)n, -1);
     for (uint32_t k = 0; k < kNumKinds; ++k) data_[k] = st;
@@ -806,9 +821,12 @@ class HipDevice : public Device {
     for (auto& e : dep_events_)
       if (chk(hipEventCreateWithFlags(&e, hipEventDisableTiming))) return MW_EHIP;
     // the LDS-staged reduce kernel takes up to 8 ranks x 16 KiB of dynamic LDS, above the 64 KiB default limit
-    if (chk(hipFuncSetAttribute(reinterpret_cast<const void*>(&mw_k_reduce<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxBufs * kReduceWG * 16)))
-      return MW_EHIP;
+    const void* lds_kernels[3] = {reinterpret_cast<const void*>(&mw_k_reduce<true, kCollCap[0]>),
+                                  reinterpret_cast<const void*>(&mw_k_reduce<true, kCollCap[1]>),
+                                  reinterpret_cast<const void*>(&mw_k_reduce<true, kCollCap[2]>)};
+    for (const void* f : lds_kernels)
+      if (chk(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxBufs * kReduceWG * 16))) return MW_EHIP;
+    arena_counts_.assign(cfg.total_slots, 0);  // the arena was zeroed above
     // The static scratch of the entry point that allocates nothing: each GPU holds its own copy of the array at
     // its own address, looked up once per device with that device current.
     if (hip_device < kMaxHipDevices && g_scratch_ptr[hip_device]) {
@@ -825,6 +843,7 @@ class HipDevice : public Device {
     chunks_.reserve(512);
     op_chunks_.reserve(512);
     chunk_bytes_.reserve(512);
+    targets_.reserve(512);
     group_of_.reserve(4096);
     static_launched_.reserve(kStaticOps);
     if (chk(hipDeviceSynchronize())) return MW_EHIP;
@@ -901,7 +920,9 @@ class HipDevice : public Device {
     //   all-reduce, 2 x 2 MiB        8 KiB  7.7 us, 16 KiB  8.3, 32 KiB  9.1
     const uint64_t groups = kind == kReduce ? 256 : 512;
     const uint32_t fill = 1u << std::min(30u, floor_log2(total_bytes / groups + 1));
-    if (kind != kReduce) return std::min(64u << 10, std::max(16u << 10, fill));
+    // Copies and fan-outs: never below 32 KiB, so that the small messages of latency-bound traffic are one chunk
+    // each and complete without the arrival counter.
+    if (kind != kReduce) return std::min(64u << 10, std::max(32u << 10, fill));
     static const uint32_t all_kib[kMaxBufs + 1] = {32, 32, 32, 16, 12, 8, 8, 8, 8};
     static const uint32_t root_kib[kMaxBufs + 1] = {48, 48, 48, 32, 24, 24, 16, 16, 12};
     const uint32_t best = (all_ranks_written ? all_kib : root_kib)[std::min<uint32_t>(nbuf, kMaxBufs)] << 10;
@@ -1064,12 +1085,19 @@ class HipDevice : public Device {
       chunks += chunks_[(size_t)i];
     }
     if (chunks == 0 || chunks > 0x7FFFFFFFull) return fail_inval();
+    // Per operation: its chunk count, and the arrival count at which it is complete -- the slot's running total
+    // (counts_) plus its chunks.  An operation of one chunk does not touch the counter.
     op_chunks_.resize((size_t)n);
+    targets_.resize((size_t)n);
     for (int i = 0; i < n;) {
       int j = i;
       uint32_t sum = 0;
       while (j < n && ents_[(size_t)j].group == ents_[(size_t)i].group) sum += chunks_[(size_t)j++];
-      for (int k = i; k < j; ++k) op_chunks_[(size_t)k] = sum;
+      const uint32_t target = counts_[ents_[(size_t)i].slot] + (sum > 1 ? sum : 0);
+      for (int k = i; k < j; ++k) {
+        op_chunks_[(size_t)k] = sum;
+        targets_[(size_t)k] = target;
+      }
       i = j;
     }
     hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -1078,61 +1106,87 @@ class HipDevice : public Device {
       e1 = prof_event();
       if (chk(hipEventRecord(e0, data_[kind]))) return MW_EHIP;
     }
-    uint32_t at = 0;
+    const int* caps = kind == kCopy ? kCopyCap : kCollCap;
+    const int tier = n <= caps[0] ? 0 : n <= caps[1] ? 1 : 2;
     if (kind == kCopy) {
-      CopyArgs& a = copy_args_;
-      a.n = (uint32_t)n;
-      a.chunk_shift = floor_log2(launch_chunk);
-      a.rotate = 1;
-      for (int i = 0; i < n; ++i) {
-        const Ent& e = ents_[(size_t)i];
-        a.first_chunk[i] = at;
-        at += chunks_[(size_t)i];
-        a.e[i] = CopyEnt{e.buf[0], e.buf[1], e.nbytes, e.slot, e.gen, e.world_id, e.world_epoch,
-                         op_chunks_[(size_t)i], e.flags};
-      }
-      a.first_chunk[n] = at;
-      hipLaunchKernelGGL(mw_k_copy, dim3(at), dim3(kCopyWG), 0, data_[kind], a, cur_slots_, cur_flags_);
+      const uint32_t shift = floor_log2(launch_chunk);
+      if (tier == 0) launch_copy<kCopyCap[0]>(shift);
+      else if (tier == 1) launch_copy<kCopyCap[1]>(shift);
+      else launch_copy<kCopyCap[2]>(shift);
     } else {
-      CollArgs& a = coll_args_;
-      a.n = (uint32_t)n;
-      a.rotate = 1;
-      for (const Ent& e : ents_) a.rotate &= kind == kBcast || (e.flags >> 24) != (1u << e.nbuf) - 1u;
-      for (int i = 0; i < n; ++i) {
-        const Ent& e = ents_[(size_t)i];
-        a.first_chunk[i] = at;
-        at += chunks_[(size_t)i];
-        CollEnt& c = a.e[i];
-        for (int k = 0; k < kMaxBufs; ++k) c.buf[k] = e.buf[k];
-        c.nbytes = e.nbytes;
-        c.slot = e.slot;
-        c.gen = e.gen;
-        c.nbuf = e.nbuf;
-        c.chunk_bytes = chunk_bytes_[(size_t)i];
-        c.world_id = e.world_id;
-        c.world_epoch = e.world_epoch;
-        c.op_chunks = op_chunks_[(size_t)i];
-        c.flags = e.flags;
-      }
-      a.first_chunk[n] = at;
-      if (kind == kBcast) {
-        hipLaunchKernelGGL(mw_k_bcast, dim3(at), dim3(kCopyWG), 0, data_[kind], a, cur_slots_, cur_flags_);
-      } else if (cfg_.reduce_lds) {
-        uint32_t lds = 0;
-        for (int i = 0; i < n; ++i) lds = std::max(lds, a.e[i].nbuf * lds_stride(a.e[i].chunk_bytes) * 16u);
-        hipLaunchKernelGGL(mw_k_reduce<true>, dim3(at), dim3(kReduceWG), lds, data_[kind], a, cur_slots_, cur_flags_);
-      } else {
-        hipLaunchKernelGGL(mw_k_reduce<false>, dim3(at), dim3(kReduceWG), 0, data_[kind], a, cur_slots_, cur_flags_);
-      }
+      if (tier == 0) launch_coll<kCollCap[0]>(kind);
+      else if (tier == 1) launch_coll<kCollCap[1]>(kind);
+      else launch_coll<kCollCap[2]>(kind);
     }
     if (chk(hipGetLastError())) return MW_EHIP;
     if (profiling_) {
       if (chk(hipEventRecord(e1, data_[kind]))) return MW_EHIP;
       prof_.push_back(ProfRec{kind, e0, e1, total_bytes});
     }
-    for (const Ent& e : ents_) launched_[e.group] = 1;  // group = index of the operation in this launch call
+    for (int i = 0; i < n; ++i) {
+      const Ent& e = ents_[(size_t)i];
+      counts_[e.slot] = targets_[(size_t)i];  // the launch is enqueued: its chunks will be counted in
+      launched_[e.group] = 1;                 // group = index of the operation in this launch call
+    }
     ents_.clear();
     return MW_OK;
+  }
+
+  template <int CAP>
+  void launch_copy(uint32_t shift) {
+    static CopyArgs<CAP> a;  // launches are serialised by the library's lock
+    const int n = (int)ents_.size();
+    uint32_t at = 0;
+    a.n = (uint32_t)n;
+    a.chunk_shift = shift;
+    a.rotate = 1;
+    for (int i = 0; i < n; ++i) {
+      const Ent& e = ents_[(size_t)i];
+      a.first_chunk[i] = at;
+      at += chunks_[(size_t)i];
+      a.e[i] = CopyEnt{e.buf[0], e.buf[1], e.nbytes, e.slot, e.gen, e.world_id, e.world_epoch,
+                       op_chunks_[(size_t)i], e.flags, targets_[(size_t)i], 0};
+    }
+    a.first_chunk[n] = at;
+    hipLaunchKernelGGL(mw_k_copy<CAP>, dim3(at), dim3(kCopyWG), 0, data_[kCopy], a, cur_slots_, cur_flags_);
+  }
+
+  template <int CAP>
+  void launch_coll(uint32_t kind) {
+    static CollArgs<CAP> a;
+    const int n = (int)ents_.size();
+    uint32_t at = 0;
+    a.n = (uint32_t)n;
+    a.rotate = 1;
+    for (const Ent& e : ents_) a.rotate &= kind == kBcast || (e.flags >> 24) != (1u << e.nbuf) - 1u;
+    for (int i = 0; i < n; ++i) {
+      const Ent& e = ents_[(size_t)i];
+      a.first_chunk[i] = at;
+      at += chunks_[(size_t)i];
+      CollEnt& c = a.e[i];
+      for (int k = 0; k < kMaxBufs; ++k) c.buf[k] = e.buf[k];
+      c.nbytes = e.nbytes;
+      c.slot = e.slot;
+      c.gen = e.gen;
+      c.nbuf = e.nbuf;
+      c.chunk_bytes = chunk_bytes_[(size_t)i];
+      c.world_id = e.world_id;
+      c.world_epoch = e.world_epoch;
+      c.op_chunks = op_chunks_[(size_t)i];
+      c.flags = e.flags;
+      c.target = targets_[(size_t)i];
+      c.pad = 0;
+    }
+    a.first_chunk[n] = at;
+    if (kind == kBcast) {
+      hipLaunchKernelGGL(mw_k_bcast<CAP>, dim3(at), dim3(kCopyWG), 0, data_[kind], a, cur_slots_, cur_flags_);
+    } else if (cfg_.reduce_lds) {
+      uint32_t lds = 0;
+      for (int i = 0; i < n; ++i) lds = std::max(lds, a.e[i].nbuf * lds_stride(a.e[i].chunk_bytes) * 16u);
+      hipLaunchKernelGGL((mw_k_reduce<true, CAP>), dim3(at), dim3(kReduceWG), lds, data_[kind], a, cur_slots_, cur_flags_);
+    } else {
+      hipLaunchKernelGGL((mw_k_reduce<false, CAP>), dim3(at), dim3(kReduceWG), 0, data_[kind], a, cur_slots_, cur_flags_);
+    }
   }
 
   int fail_inval() {
@@ -1180,9 +1234,10 @@ class HipDevice : public Device {
   std::vector<void*> dep_streams_, waited_;  // distinct caller streams of the current launch() call
   std::vector<uint8_t> dep_busy_;            // ... and whether each still had work pending
   std::vector<int> group_of_;                // per operation: index of its first busy stream, or -1
-  std::vector<uint32_t> chunks_, op_chunks_, chunk_bytes_;
-  CopyArgs copy_args_{};
-  CollArgs coll_args_{};
+  std::vector<uint32_t> chunks_, op_chunks_, chunk_bytes_, targets_;
+  std::vector<uint32_t> arena_counts_;          // per arena slot: chunks counted in so far (what the device counter will reach)
+  uint32_t static_counts_[kStaticOps] = {};     // the same for the static scratch, whose counters every call zeroes
+  uint32_t* counts_ = nullptr;                  // the one the current launch uses
 };
 
 }  // namespace

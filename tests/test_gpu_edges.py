@@ -492,10 +492,11 @@ def test_ring_journal_header_and_isolation_across_abort(torch, mw):
     assert s["bufs"][:2] == (bufs[40][0].data_ptr(), bufs[40][1].data_ptr()) and s["nbytes"] == n
     assert (s["kind"], s["nbuf"], s["world"], s["epoch"], s["dtype"]) == (0, 2, 40, 0, mw.MW_BF16)
     assert s["nchunks"] * s["chunk"] >= n > (s["nchunks"] - 1) * s["chunk"]
-    assert s["arrived"] == 0 and s["done_gen"] == s["gen"]  # counter re-armed, completion published
+    assert s["nchunks"] > 1 and s["arrived"] == s["nchunks"] and s["done_gen"] == s["gen"]  # every chunk counted in, completion published
     r42 = mw.mw_debug_ring_read(42)
     s42 = [x for x in (_slot_fields(r42, i) for i in range(128)) if x["gen"]][0]
     assert (s42["kind"], s42["nbuf"], s42["nbytes"], s42["world"]) == (2, 3, 4000, 42)
+    assert s42["nchunks"] == 1 and s42["arrived"] == 0 and s42["done_gen"] == s42["gen"]  # one chunk: no counting
     # abort world 40 while one of its operations waits for a peer: nothing else changes
     before = mw.mw_debug_arena_hash(40)
     snap41, snap42 = mw.mw_debug_ring_read(41), mw.mw_debug_ring_read(42)
