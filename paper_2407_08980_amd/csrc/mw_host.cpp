@@ -16,6 +16,8 @@
 
 #include <atomic>
 #include <chrono>
+#include <climits>
+#include <cstdint>
 #include <cstring>
 #include <deque>
 #include <memory>
@@ -81,10 +83,14 @@ struct OpRec {  // an operation all of whose sides have been posted
   uint8_t state;
 };
 
+// One entry of the handle table.  Every field is written under the library lock; mw_poll also reads them WITHOUT
+// the lock (poll_fast), as a sequence lock on `gen`: an entry is recycled by gen = 0, new fields, gen = new.
 struct HandleEnt {
-  uint32_t gen = 0;
-  int32_t status = MW_DONE;  // a never-used entry counts as terminal: it can be allocated
-  uint32_t op = kNone;
+  std::atomic<uint32_t> gen{0};
+  std::atomic<int32_t> status{MW_DONE};   // a never-used entry counts as terminal: it can be allocated
+  std::atomic<uint32_t> op{kNone};        // record of the matched operation, kNone while waiting for a peer
+  std::atomic<uint32_t> flag_slot{kNone}; // once launched: the ring slot whose completion word ...
+  std::atomic<uint32_t> flag_gen{0};      // ... reaching this generation means the operation is complete
 };
 
 struct Context {
@@ -104,7 +110,9 @@ struct Context {
   std::vector<uint32_t> free_ops;
   std::deque<uint32_t> ready;  // op records waiting for a launch, in match order
 
-  std::vector<HandleEnt> handles;
+  std::unique_ptr<HandleEnt[]> handles;  // fixed size: entries are read without the lock
+  uint32_t n_handles = 0;
+  uint32_t last_handle_gen = 0;  // generations are unique across the table, so a recycled entry never repeats one
   uint32_t handle_cursor = 0;
 
   // watchdog (Sec. 3.3): per-worker heartbeat epochs and times
@@ -123,6 +131,33 @@ struct Context {
 
 std::mutex g_lock;
 std::unique_ptr<Context> g_ctx;
+// Lock-free polls: g_fast is the context while it may be read without the lock.  A poll counts itself in around
+// its reads and mw_shutdown clears g_fast, then waits for the counts to drain before it frees anything (store then
+// load on one side, add then load on the other, all sequentially consistent: either the poll sees no context or the
+// shutdown sees the poll).  The count is striped over cache lines by thread so that busy-polling threads do not
+// pass one line around (one shared counter: 870 ns per poll with 8 threads polling; striped: see tests/poll_contention.cpp).
+std::atomic<Context*> g_fast{nullptr};
+constexpr int kReaderStripes = 64;
+struct alignas(64) ReaderStripe {
+  std::atomic<int> n{0};
+};
+ReaderStripe g_fast_readers[kReaderStripes];
+std::atomic<unsigned> g_next_stripe{0};
+
+inline ReaderStripe& my_stripe() {
+  thread_local unsigned mine = g_next_stripe.fetch_add(1, std::memory_order_relaxed) % kReaderStripes;
+  return g_fast_readers[mine];
+}
+
+struct FastRead {  // RAII: the context for one lock-free read, or nullptr
+  ReaderStripe& stripe;
+  Context* c;
+  FastRead() : stripe(my_stripe()) {
+    stripe.n.fetch_add(1, std::memory_order_seq_cst);
+    c = g_fast.load(std::memory_order_seq_cst);
+  }
+  ~FastRead() { stripe.n.fetch_sub(1, std::memory_order_release); }
+};
 // watchdog thread: wakes every period, takes g_lock, inspects the heartbeat table
 std::thread g_wd_thread;
 std::mutex g_wd_mu;  // guards g_wd_thread / g_wd_running
@@ -134,16 +169,20 @@ inline mw_handle make_handle(uint32_t slot, uint32_t gen) { return ((uint64_t)ge
 
 // ---- handles ---------------------------------------------------------------------------------
 int alloc_handle(Context& c, uint32_t* out) {
-  const uint32_t cap = (uint32_t)c.handles.size();
+  const uint32_t cap = c.n_handles;
   for (uint32_t tries = 0; tries < cap; ++tries) {
     uint32_t s = c.handle_cursor;
     c.handle_cursor = (s + 1 == cap) ? 0 : s + 1;
     HandleEnt& e = c.handles[s];
-    if (e.status == MW_PENDING) continue;  // still live: never recycle
-    e.gen += 1;
-    if (e.gen == 0) e.gen = 1;
-    e.status = MW_PENDING;
-    e.op = kNone;
+    if (e.status.load(std::memory_order_relaxed) == MW_PENDING) continue;  // still live: never recycle
+    uint32_t g = e.gen.load(std::memory_order_relaxed) + 1;
+    if (g == 0) g = 1;
+    e.gen.store(0, std::memory_order_relaxed);  // lock-free readers of the old handle back off from here on
+    std::atomic_thread_fence(std::memory_order_release);
+    e.status.store(MW_PENDING, std::memory_order_relaxed);
+    e.op.store(kNone, std::memory_order_relaxed);
+    e.flag_slot.store(kNone, std::memory_order_relaxed);
+    e.gen.store(g, std::memory_order_release);
     *out = s;
     return MW_OK;
   }
@@ -152,8 +191,8 @@ int alloc_handle(Context& c, uint32_t* out) {
 
 inline void finish_handle(Context& c, uint32_t hslot, int status) {
   HandleEnt& e = c.handles[hslot];
-  e.status = status;
-  e.op = kNone;
+  e.status.store(status, std::memory_order_release);
+  e.op.store(kNone, std::memory_order_relaxed);
 }
 
 // ---- ring slots --------------------------------------------------------------------------------
@@ -265,6 +304,11 @@ int flush_locked(Context& c) {
       op.state = kOpInflight;
       w.queued -= 1;
       w.inflight.push_back(opi);
+      for (int k = 0; k < op.n_handles; ++k) {  // from here on a poll of these handles needs no lock until the flag flips
+        HandleEnt& e = c.handles[op.handles[k]];
+        e.flag_gen.store(op.l.gen, std::memory_order_relaxed);
+        e.flag_slot.store(op.l.slot, std::memory_order_release);
+      }
     } else {
       slot_release(w, op.l.slot - w.first_slot);
       c.ready.push_front(opi);
@@ -293,7 +337,7 @@ int enqueue_op(Context& c, uint32_t wi, const LaunchOp& l, const Post* posts, in
   for (int i = 0; i < n_posts; ++i) {
     const Post& p = posts[i];
     op.handles[op.n_handles++] = p.hslot;
-    c.handles[p.hslot].op = opi;
+    c.handles[p.hslot].op.store(opi, std::memory_order_release);
     if (p.stream != MW_STREAM_NONE) {
       bool seen = false;
       for (int k = 0; k < op.n_streams; ++k) seen |= (op.streams[k] == p.stream);
@@ -322,7 +366,7 @@ int post_p2p_locked(Context& c, bool is_send, int world_id, int src, int dst, co
   uint32_t hs;
   int rc = alloc_handle(c, &hs);
   if (rc != MW_OK) return rc;
-  *out = make_handle(hs, c.handles[hs].gen);
+  *out = make_handle(hs, c.handles[hs].gen.load(std::memory_order_relaxed));
   Post me{hs, (uint64_t)(uintptr_t)buf, (uint64_t)count, (uint32_t)dtype, stream, 0};
   PairQ& q = w.pairs[(uint32_t)src * MW_MAX_RANKS + (uint32_t)dst];
   std::deque<Post>& theirs = is_send ? q.recvs : q.sends;
@@ -383,7 +427,7 @@ int post_coll_locked(Context& c, uint32_t kind, int world_id, int rank, int root
   uint32_t hs;
   int rc = alloc_handle(c, &hs);
   if (rc != MW_OK) return rc;
-  *out = make_handle(hs, c.handles[hs].gen);
+  *out = make_handle(hs, c.handles[hs].gen.load(std::memory_order_relaxed));
   uint32_t seq = w.coll_next[rank]++;
   uint32_t idx = seq - w.coll_base;
   while (w.coll.size() <= idx) w.coll.emplace_back();
@@ -523,14 +567,41 @@ void stop_watchdog_thread() {  // called WITHOUT g_lock held
   if (t.joinable()) t.join();
 }
 
+// A poll answered without the library lock: terminal states (they are sticky), operations still waiting for a
+// peer, and -- the case every busy-waiting worker spins in (Sec. 3.3) -- operations in flight whose completion
+// word has not flipped yet.  Everything that changes a table (launching a queued operation, retiring a completed
+// one) and every error goes to the locked path.  Returns false if the locked path has to answer.
+inline bool poll_fast(Context& c, mw_handle h, int* state) {
+  const uint32_t slot = (uint32_t)(h & 0xFFFFFFFFu), gen = (uint32_t)(h >> 32);
+  if (slot >= c.n_handles || gen == 0) return false;
+  HandleEnt& e = c.handles[slot];
+  if (e.gen.load(std::memory_order_acquire) != gen) return false;
+  const int32_t st = e.status.load(std::memory_order_acquire);
+  const uint32_t op = e.op.load(std::memory_order_relaxed);
+  const uint32_t fs = e.flag_slot.load(std::memory_order_acquire);
+  const uint32_t fg = e.flag_gen.load(std::memory_order_relaxed);
+  std::atomic_thread_fence(std::memory_order_acquire);
+  if (e.gen.load(std::memory_order_relaxed) != gen) return false;  // recycled while we looked
+  if (st != MW_PENDING) {
+    *state = st;
+    return true;
+  }
+  if (op == kNone || (fs != kNone && c.dev->flag(fs) != fg)) {
+    *state = MW_PENDING;
+    return true;
+  }
+  return false;
+}
+
 int poll_locked(Context& c, mw_handle h) {
   uint32_t slot = (uint32_t)(h & 0xFFFFFFFFu), gen = (uint32_t)(h >> 32);
-  if (slot >= c.handles.size() || gen == 0) return MW_EBADHANDLE;
+  if (slot >= c.n_handles || gen == 0) return MW_EBADHANDLE;
   HandleEnt& e = c.handles[slot];
-  if (e.gen != gen) return MW_EBADHANDLE;
-  if (e.status != MW_PENDING) return e.status;
-  if (e.op == kNone) return MW_PENDING;  // still waiting for a peer
-  uint32_t opi = e.op;
+  if (e.gen.load(std::memory_order_relaxed) != gen) return MW_EBADHANDLE;
+  const int32_t status = e.status.load(std::memory_order_relaxed);
+  if (status != MW_PENDING) return status;
+  if (e.op.load(std::memory_order_relaxed) == kNone) return MW_PENDING;  // still waiting for a peer
+  uint32_t opi = e.op.load(std::memory_order_relaxed);
   if (c.ops[opi].state == kOpQueued) {
     int rc = flush_locked(c);
     if (rc != MW_OK) return rc;
@@ -571,8 +642,10 @@ int mw_init(int hip_device, int n_workers) {
   c->failed.assign((size_t)n_workers, 0);
   c->slot_gen.assign(c->cfg.total_slots, 0);
   for (uint32_t r = c->max_rings; r-- > 0;) c->free_rings.push_back(r);
-  c->handles.resize((size_t)g_cfg_handles);
+  c->handles.reset(new HandleEnt[(size_t)g_cfg_handles]);
+  c->n_handles = (uint32_t)g_cfg_handles;
   g_ctx = std::move(c);
+  g_fast.store(g_ctx.get(), std::memory_order_release);
   return MW_OK;
 }
 
@@ -580,6 +653,9 @@ int mw_shutdown(void) {
   stop_watchdog_thread();
   std::lock_guard<std::mutex> g(g_lock);
   if (!g_ctx) return MW_ENOTINIT;
+  g_fast.store(nullptr, std::memory_order_seq_cst);  // no new lock-free reader gets the context ...
+  for (ReaderStripe& r : g_fast_readers)  // ... and the current ones leave
+    while (r.n.load(std::memory_order_seq_cst) != 0) std::this_thread::yield();
   flush_locked(*g_ctx);
   g_ctx->dev->sync();
   g_ctx->dev->shutdown();
@@ -836,7 +912,6 @@ int mw_post_many_noalloc(const mw_post_desc* posts, int n, void* hip_stream) {
   LaunchOp ops[MW_NOALLOC_MAX_OPS];
   int n_ops = 0;
   bool used[MW_NOALLOC_MAX_POSTS] = {};
-  uint32_t seq[MW_NOALLOC_MAX_POSTS] = {};  // collectives: which collective of its (world, rank) a post is
   const World* world_of[MW_NOALLOC_MAX_POSTS] = {};
   for (int i = 0; i < n; ++i) {  // validate every post as its posting call would
     const mw_post_desc& p = posts[i];
@@ -862,8 +937,6 @@ int mw_post_many_noalloc(const mw_post_desc* posts, int n, void* hip_stream) {
         if ((need1 && !p.buf) || (need2 && !p.buf2)) return MW_EINVAL;
       }
       if ((k == opAllReduce || k == opReduce) && ((uintptr_t)p.buf % item_size((uint32_t)p.dtype)) != 0) return MW_EINVAL;
-      for (int j = 0; j < i; ++j)
-        seq[i] += posts[j].kind > MW_POST_RECV && posts[j].world_id == p.world_id && posts[j].a == p.a;
     }
     if (w.state == MW_BROKEN) return MW_EBROKEN;
   }
@@ -899,9 +972,10 @@ int mw_post_many_noalloc(const mw_post_desc* posts, int n, void* hip_stream) {
       const int root = rooted(k) ? p.b : 0;
       int side[kMaxBufs];
       for (int r = 0; r < nr; ++r) side[r] = -1;
+      // the k-th collective a rank posts belongs to the world's k-th collective: with the earlier collectives
+      // taken, that is every rank's first collective post that is still free
       for (int j = i; j < n; ++j)
-        if (!used[j] && posts[j].kind > MW_POST_RECV && posts[j].world_id == p.world_id && seq[j] == seq[i] &&
-            side[posts[j].a] < 0)
+        if (!used[j] && posts[j].kind > MW_POST_RECV && posts[j].world_id == p.world_id && side[posts[j].a] < 0)
           side[posts[j].a] = j;
       for (int r = 0; r < nr; ++r) {
         if (side[r] < 0) return MW_EINVAL;  // a rank did not post this collective
@@ -960,17 +1034,37 @@ int mw_post_many_noalloc(const mw_post_desc* posts, int n, void* hip_stream) {
 }
 
 int mw_poll(mw_handle h) {
+  {
+    FastRead r;
+    int st;
+    if (r.c && poll_fast(*r.c, h, &st)) return st;
+  }
   std::lock_guard<std::mutex> g(g_lock);
   if (!g_ctx) return MW_ENOTINIT;
   return poll_locked(*g_ctx, h);
 }
 
 int mw_poll_many(const mw_handle* handles, int n, int* states) {
+  if (n < 0 || (n > 0 && (!handles || !states))) return MW_EINVAL;
+  int pending = 0, slow = 0;
+  {
+    FastRead r;
+    if (r.c) {
+      for (int i = 0; i < n; ++i) {
+        if (poll_fast(*r.c, handles[i], &states[i])) {
+          pending += states[i] == MW_PENDING;
+        } else {
+          states[i] = INT32_MIN;  // to be answered under the lock
+          ++slow;
+        }
+      }
+      if (!slow) return pending;
+    }
+  }
   std::lock_guard<std::mutex> g(g_lock);
   if (!g_ctx) return MW_ENOTINIT;
-  if (n < 0 || (n > 0 && (!handles || !states))) return MW_EINVAL;
-  int pending = 0;
   for (int i = 0; i < n; ++i) {
+    if (slow && states[i] != INT32_MIN) continue;
     states[i] = poll_locked(*g_ctx, handles[i]);
     pending += states[i] == MW_PENDING;
   }
@@ -1046,7 +1140,7 @@ long mw_config_get(const char* key) {
 
 int mw_handle_capacity(void) {
   std::lock_guard<std::mutex> g(g_lock);
-  return g_ctx ? (int)g_ctx->handles.size() : (int)g_cfg_handles;
+  return g_ctx ? (int)g_ctx->n_handles : (int)g_cfg_handles;
 }
 
 int mw_last_hip_error(void) {

@@ -134,3 +134,63 @@ def test_reduce_every_root(torch, mw, n, dtype, lds):
                         assert np.array_equal(d[r][1].cpu().numpy(), host[r]), "a non-root buffer was written"
     finally:
         mw.mw_config_set("reduce_lds", 0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_real_valued_sums_forwarded_through_further_operations(torch, mw, dtype):
+    """A buffer that has been all-reduced is sent on, broadcast, reduced again and all-reduced again, with N(0,1)
+    values.  The device accumulates in fp32 in ascending rank order, so on the oracle's side each step continues
+    from the bytes of its ascending-order fp32 sum: every step is then compared bit for bit, and every sum also
+    against the float64 sum of the bytes that went into it, within the summation tolerance."""
+    count = 300007
+    isz = 4 if dtype == "f32" else 2
+    dt = mw.DTYPES[dtype]
+    rng = np.random.default_rng(77 if dtype == "f32" else 78)
+
+    def draw():
+        x = rng.standard_normal(count).astype(np.float32)
+        return x.view(np.uint8).copy() if dtype == "f32" else oracle.f32_to_bf16_bits(x).view(np.uint8).copy()
+
+    def check_sum(got, inputs, what):
+        s, sabs = oracle.allreduce_sum_f64(inputs, count, dtype)
+        ok, worst = oracle.allreduce_within_tolerance(got, s, sabs, count, dtype)
+        assert ok, (what, worst)
+        want = oracle.allreduce_sum_ordered(inputs, count, dtype)
+        assert np.array_equal(got, want), what
+        return want
+
+    mw.mw_world_create(0, [0, 1, 2, 3])   # the first sum
+    mw.mw_world_create(1, [0, 4])         # forwards it
+    mw.mw_world_create(2, [4, 5, 6])      # broadcasts it, then reduces it with fresh tensors
+    mw.mw_world_create(3, [5, 6])         # sums the reduction's result once more
+    x = [draw() for _ in range(4)]
+    d = [dev(torch, h)[1] for h in x]
+    assert wait(mw, [mw.mw_allreduce_sum(0, r, d[r].data_ptr(), count, dt) for r in range(4)]) == [mw.MW_DONE] * 4
+    s1 = check_sum(d[0].cpu().numpy(), x, "first all-reduce")
+    for r in range(1, 4):
+        assert np.array_equal(d[r].cpu().numpy(), s1)
+    # worker 0 sends its sum to worker 4
+    fwd = dev(torch, np.full(count * isz, 0xA5, np.uint8))[1]
+    hs = [mw.mw_send(1, 0, 1, d[0].data_ptr(), count, dt), mw.mw_recv(1, 0, 1, fwd.data_ptr(), count, dt)]
+    assert wait(mw, hs) == [mw.MW_DONE] * 2
+    assert np.array_equal(fwd.cpu().numpy(), oracle.copy_result(s1))
+    # worker 4 broadcasts it in world 2
+    others = [dev(torch, np.full(count * isz, 0xA5, np.uint8))[1] for _ in range(2)]
+    bufs = [fwd] + others
+    assert wait(mw, [mw.mw_broadcast(2, r, 0, bufs[r].data_ptr(), count, dt) for r in range(3)]) == [mw.MW_DONE] * 3
+    want = oracle.broadcast_result([s1, None, None], 0)
+    for r in range(3):
+        assert np.array_equal(bufs[r].cpu().numpy(), want[r]), r
+    # ranks 1 and 2 add fresh tensors of their own into the copy they received, reduced onto rank 2
+    fresh = [draw(), draw()]
+    others[0].copy_(torch.from_numpy(fresh[0]).cuda())
+    torch.cuda.synchronize()
+    inputs = [s1, fresh[0], s1]
+    assert wait(mw, [mw.mw_reduce_sum(2, r, 2, bufs[r].data_ptr(), count, dt) for r in range(3)]) == [mw.MW_DONE] * 3
+    s2 = check_sum(bufs[2].cpu().numpy(), inputs, "reduce of forwarded sums")
+    assert np.array_equal(bufs[0].cpu().numpy(), s1) and np.array_equal(bufs[1].cpu().numpy(), fresh[0])  # only read
+    # workers 5 and 6 all-reduce: a fresh tensor and the reduction's result
+    last = [dev(torch, fresh[1])[1], bufs[2]]
+    assert wait(mw, [mw.mw_allreduce_sum(3, r, last[r].data_ptr(), count, dt) for r in range(2)]) == [mw.MW_DONE] * 2
+    s3 = check_sum(last[0].cpu().numpy(), [fresh[1], s2], "all-reduce of a reduction's result")
+    assert np.array_equal(last[1].cpu().numpy(), s3)

@@ -1,9 +1,10 @@
 """The workloads at their full sizes on the GPU, in the launch configuration bench.py times.
 
 The oracle cannot hold these runs in host memory, so: terminal statuses are compared for every
-operation (the oracle runs the whole trace without data), received == sent is checked on the
-device for every checked message, and seeded byte windows of those messages are compared with
-what the oracle computes from the input recipe.
+operation (the oracle runs the whole trace without data); on the steps that between them use every
+source tensor of every world (and on the last steps) the WHOLE destination is brought to the host and
+compared with what the oracle computes from the input recipe, 64 MiB at a time; on the other checked
+steps received == sent is checked on the device and seeded byte windows against the oracle.
 """
 
 import numpy as np
@@ -40,6 +41,19 @@ def window_of(spec, pools, lo, n):
     return pool_slice(pools.get(spec.init[1]), spec.init[1], spec.init[2] + lo // ITEMSIZE[spec.init[1]], n)
 
 
+def assert_whole_buffer(tensor, src_spec, pools, what, piece=64 << 20):
+    """Every byte of a device buffer against the oracle's copy of its source's recipe bytes."""
+    nbytes = src_spec.nbytes
+    assert tensor.numel() == nbytes
+    for lo in range(0, nbytes, piece):
+        n = min(piece, nbytes - lo)
+        want = oracle.copy_result(window_of(src_spec, pools, lo, n))
+        got = tensor[lo:lo + n].cpu().numpy()
+        if not np.array_equal(got, want):
+            bad = np.flatnonzero(got != want)
+            raise AssertionError(f"{what}: {bad.size} bytes differ from the oracle in [{lo}, {lo + n}), first at {lo + bad[0]}")
+
+
 def windows(nbytes, rng, k=6, width=1 << 16):
     los = [0, max(0, nbytes - width)] + [int(x) & ~1 for x in rng.integers(0, max(1, nbytes - width), size=k)]
     return [(lo, min(width, nbytes - lo)) for lo in los]
@@ -62,6 +76,9 @@ def test_config2_full_size(gpu, host_pools):
         n_checked[0] += 1
         src_id = world * 4 + s % 4
         assert s % 2 == slot
+        if s in (0, 1, 2, 47, 49):  # between them: all four source tensors of every world, and the last step
+            assert_whole_buffer(bufs[op.buf], t.bufs[src_id], host_pools, f"world {world} step {s}")
+            return
         assert torch.equal(bufs[op.buf], bufs[src_id]), f"world {world} step {s}: received != sent"
         for lo, n in windows(t.bufs[op.buf].nbytes, rng):
             want = oracle.copy_result(window_of(t.bufs[src_id], host_pools, lo, n))
@@ -93,6 +110,9 @@ def test_config4_full_size_fault_isolation(gpu, host_pools):
             assert bool((bufs[op.buf] == 0xA5).all()), f"step {s}: the broken world's destination was written"
             return
         src_id = world * 4 + s % 4
+        if s in (0, 1, 98, 99, 299):  # all four source tensors of every world (98, 99 use the third and fourth), and the last step
+            assert_whole_buffer(bufs[op.buf], t.bufs[src_id], host_pools, f"world {world} step {s}")
+            return
         assert torch.equal(bufs[op.buf], bufs[src_id]), f"world {world} step {s}: received != sent"
         for lo, n in windows(t.bufs[op.buf].nbytes, rng, k=2):
             want = oracle.copy_result(window_of(t.bufs[src_id], host_pools, lo, n))
@@ -158,6 +178,12 @@ def test_headline_workload_in_the_benchmarks_own_loop(gpu, host_pools):
             for s in (first + 1, first + 2):  # the two steps whose destinations are still intact
                 for w in range(bench.N_WORLDS):
                     d, src = wl.dst[w][s % 2], wl.src[w][s % bench.POOL_K]
+                    if s == 8:  # the last step: every byte of every world's destination against the oracle
+                        for lo in range(0, wl.nbytes, 64 << 20):
+                            n = min(64 << 20, wl.nbytes - lo)
+                            want = oracle.copy_result(pool_slice(pool, "bf16", wl.offsets[w][s % bench.POOL_K] + lo // 2, n))
+                            assert np.array_equal(d[lo:lo + n].cpu().numpy(), want), (w, s, lo)
+                        continue
                     assert torch.equal(d, src), (w, s)
                     for lo, n in windows(wl.nbytes, rng, k=2):
                         want = oracle.copy_result(pool_slice(pool, "bf16", wl.offsets[w][s % bench.POOL_K] + lo // 2, n))

@@ -30,7 +30,7 @@ MUTANTS = [
     ("broadcast descriptor starts with rank 0 instead of the root", "        l.buf[at++] = f.post[rt].buf;\n        for (int r = 0; r < n; ++r)\n          if (r != rt) l.buf[at++] = f.post[r].buf;",
      "        for (int r = 0; r < n; ++r) l.buf[at++] = f.post[r].buf;"),
     ("copy descriptor has source and destination swapped", "  l.buf[0] = pair[0].buf;\n  l.buf[1] = pair[1].buf;", "  l.buf[0] = pair[1].buf;\n  l.buf[1] = pair[0].buf;"),
-    ("live handles are recycled", "    if (e.status == MW_PENDING) continue;  // still live: never recycle\n", ""),
+    ("live handles are recycled", "    if (e.status.load(std::memory_order_relaxed) == MW_PENDING) continue;  // still live: never recycle\n", ""),
     ("ring slots are never given back", "  slot_release(w, op.l.slot - w.first_slot);\n  op.state = kOpFree;", "  op.state = kOpFree;"),
     ("completion generation is not advanced", "uint32_t gen = c.slot_gen[slot] + 1;", "uint32_t gen = c.slot_gen[slot] + (slot & 1);"),
     ("matched operations of an aborted world are dropped", "  // Operations that already had all their sides are delivered: launch them now so that they retire.\n  int rc2 = flush_locked(c);",
@@ -38,6 +38,13 @@ MUTANTS = [
     ("watchdog takes a report exactly as old as the timeout for a miss", "!(now - c.last_beat[k] > timeout)", "!(now - c.last_beat[k] >= timeout)"),
     ("watchdog aborts the worlds of every watched worker", "    for (uint32_t wi : c.worlds_of_worker[k]) abort_world_locked(c, *c.worlds[wi]);",
      "    for (size_t q = 0; q < c.beating.size(); ++q) if (c.beating[q]) for (uint32_t wi : c.worlds_of_worker[q]) abort_world_locked(c, *c.worlds[wi]);"),
+    ("a poll without the lock never looks at the completion word", "(fs != kNone && c.dev->flag(fs) != fg)", "(fs != kNone)"),
+    ("a poll without the lock takes a launched operation for a complete one", "  if (st != MW_PENDING) {\n    *state = st;\n    return true;\n  }\n  if (op == kNone",
+     "  if (st != MW_PENDING || fs != kNone) {\n    *state = fs != kNone ? MW_DONE : st;\n    return true;\n  }\n  if (op == kNone"),
+    ("the allocation-free variant pairs a side with a side of its own kind", "posts[j].kind == 1 - p.kind", "posts[j].kind == p.kind"),
+    ("the allocation-free variant lets a rank's later collective overtake its earlier one",
+     "posts[j].world_id == p.world_id && side[posts[j].a] < 0)\n          side[posts[j].a] = j;",
+     "posts[j].world_id == p.world_id)\n          side[posts[j].a] = j;"),
     ("a zero-length message waits for a launch", "  if (count == 0) {\n    finish_handle(c, hs, MW_DONE);\n    finish_handle(c, other.hslot, MW_DONE);\n    return MW_OK;\n  }\n", ""),
 ]
 
@@ -83,6 +90,7 @@ def run_host_tests(lib):
                            os.path.join(ROOT, "tests", "test_host_logic.py"),
                            os.path.join(ROOT, "tests", "test_host_vs_oracle_fuzz.py"),
                            os.path.join(ROOT, "tests", "test_watchdog.py"),
+                           os.path.join(ROOT, "tests", "test_host_noalloc.py"),
                            "-k", "not cost and not product_library and not oracle_watchdog"],
                           cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=600,
                           preexec_fn=_limit_memory)
