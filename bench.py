@@ -30,8 +30,8 @@ POOL_K = 4
 # HBM bytes per mw_k_copy launch of this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (summary in
 # profiles/mw_k_copy_config2_hbm_counters.txt).  Valid only for the kernel source it was taken with: once
 # csrc/mw_device.hip changes, `traffic` is reported as null until the counters are taken again.
-PMC_TRAFFIC = {"sha256": "5a6c92cd8285d92bfb98bb3aa1694e03bc21963e1772a728654ebc63d0e21403",
-               "bytes_per_launch": 8590988491}
+PMC_TRAFFIC = {"sha256": "25d0e8f45be859e9b4e25179e2b46eab49e53d34054bacece0df9a5f261831ef",
+               "bytes_per_launch": 8592009729}
 
 
 def parse():
