@@ -53,6 +53,7 @@ def parse():
     ap.add_argument("--depth", type=int, default=2, help="config5: windows in flight (window x depth <= 64)")
     ap.add_argument("--chunk-bytes", type=int, default=0, help="pin the kernels' chunk size (0 = chosen per launch)")
     ap.add_argument("--reduce-lds", type=int, default=0, help="config3: 1 = LDS-staged all-reduce kernel")
+    ap.add_argument("--c3-depth", type=int, default=3, help="config3: iterations in flight (each on input sets of its own)")
     ap.add_argument("--coll-launches", type=int, default=200, help="collectives: timed launches per operation")
     ap.add_argument("--coll-warmup", type=int, default=20, help="collectives: untimed launches per operation")
     ap.add_argument("--shape", type=int, nargs=3, default=list(SHAPE), help=argparse.SUPPRESS)
@@ -484,7 +485,7 @@ def run_config4(torch, mw, dev, steps, abort_step, reps):
     }
 
 
-def run_config3(torch, mw, dev, iters, reps, lds):
+def run_config3(torch, mw, dev, iters, reps, lds, depth=2):
     """Tensor-parallel partial sums: 4 worlds x 4 ranks, all-reduce of fp32 [16,4096] and [16,14336] per
     iteration, all worlds outstanding together.  Latency-bound and cache-resident (28 MiB working set)."""
     mw.mw_config_set("reduce_lds", lds)
@@ -512,18 +513,19 @@ def run_config3(torch, mw, dev, iters, reps, lds):
     def run(pbs, n_iter):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        prev = None
+        live = []
         for it in range(n_iter):
             pb = pbs[it % POOL_K]
             pb.post()
             mw.mw_flush()
-            cur = pb.pollset()
-            if prev is not None:
-                while prev.poll():
+            live.append(pb.pollset())
+            if len(live) >= depth:  # `depth` iterations in flight (each on buffers of its own)
+                ps = live.pop(0)
+                while ps.poll():
                     pass
-            prev = cur
-        while prev.poll():
-            pass
+        for ps in live:
+            while ps.poll():
+                pass
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
@@ -544,6 +546,11 @@ def run_config3(torch, mw, dev, iters, reps, lds):
     for _ in range(reps):
         sw_r.append(iters * per_iter_bytes / run(single, iters) / 1e9)
         mw_r.append(iters * per_iter_bytes / run(multi, iters) / 1e9)
+    by_depth = {}
+    want = depth
+    for depth in (1, 2, 3):  # the same loop with fewer iterations in flight, for the record
+        by_depth[str(depth)] = round(run(multi, iters) / iters * 1e6, 2)
+    depth = want
     mean = lambda v: sum(v) / len(v) if v else float("nan")
     value = iters * per_iter_bytes / secs / 1e9
     alg = 2.0 * n_ranks * op_bytes  # n reads + n writes of every payload
@@ -552,9 +559,9 @@ def run_config3(torch, mw, dev, iters, reps, lds):
         "value": round(value, 2), "ms_per_step": round(secs / iters * 1e3, 4), "steps": iters,
         "config": {"workload": "config 3: tensor-parallel partial-sum all-reduce, 4 worlds x 4 ranks, fp32 [16,4096] + "
                                "[16,14336] per iteration, all worlds concurrent (latency-bound, cache-resident)",
-                   "worlds": n_worlds, "ranks": n_ranks, "payload_dtype": "f32", "steps_in_flight": 2,
+                   "worlds": n_worlds, "ranks": n_ranks, "payload_dtype": "f32", "steps_in_flight": depth,
                    "reduce_lds": lds},
-        "us_per_iteration": round(secs / iters * 1e6, 2),
+        "us_per_iteration": round(secs / iters * 1e6, 2), "us_per_iteration_by_iterations_in_flight": by_depth,
         "us_per_iteration_with_kernel_timing": round(secs_profiled / iters * 1e6, 2),
         "algorithmic_traffic_GBps": round(2 * n_ranks * value, 1),
         "single_world_GBps": round(mean(sw_r), 2) if reps else None,
@@ -600,9 +607,26 @@ def run_config1(torch, mw, dev, reps):
                 pass
         return time.perf_counter() - t0
 
+    def run_two_in_flight(pbs):
+        """The same windows with the next one posted while the previous one is in flight."""
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        prev = None
+        for pb in pbs:
+            pb.post()
+            mw.mw_flush()
+            if prev is not None:
+                while prev.poll():
+                    pass
+            prev = pb.pollset()
+        while prev.poll():
+            pass
+        return time.perf_counter() - t0
+
     multi, single = make(False), make(True)
     for _ in range(5):
-        run(multi), run(single)
+        run(multi), run(single), run_two_in_flight(multi)
+    piped = sorted(run_two_in_flight(multi) for _ in range(max(reps, 1) * 8))
     mw_t, sw_t = [], []
     for _ in range(max(reps, 1) * 8):  # interleaved so that clock and cache state are shared
         sw_t.append(run(single))
@@ -636,6 +660,7 @@ def run_config1(torch, mw, dev, reps):
                    "payload_dtype": "f32"},
         "us_per_message_windowed": round(secs / n_msgs * 1e6, 3),
         "messages_per_s": round(n_msgs / secs),
+        "us_per_message_two_windows_in_flight": round(piped[len(piped) // 2] / n_msgs * 1e6, 3),
         "single_message_round_trip_us": {"median": round(rt[len(rt) // 2] * 1e6, 2), "p10": round(rt[len(rt) // 10] * 1e6, 2),
                                          "p90": round(rt[9 * len(rt) // 10] * 1e6, 2)},
         "single_world_GBps": round(n_msgs * count * 4 / mean(sw_t) / 1e9, 3),
@@ -1189,7 +1214,7 @@ def main():
     if args.workload == "config4":
         res = run_config4(torch, mw, dev, args.steps if args.steps != 50 else 300, args.abort_step, args.reps)
     elif args.workload == "config3":
-        res = run_config3(torch, mw, dev, args.steps if args.steps != 50 else 500, args.reps, args.reduce_lds)
+        res = run_config3(torch, mw, dev, args.steps if args.steps != 50 else 500, args.reps, args.reduce_lds, args.c3_depth)
     elif args.workload == "config1":
         res = run_config1(torch, mw, dev, args.reps)
     elif args.workload == "collectives":

@@ -1212,7 +1212,7 @@ class HipDevice : public Device {
   // boundary of one is hidden behind the other (the 4 x 4-rank all-reduce iteration went from 19.2 to
   // 12.4 us, windows of 4 MB messages gained 8 %); small launches (kernels of a few us) stay on lane 1,
   // where alternating measured 15-25 % slower.
-  static constexpr int kLanes = 3;
+  static constexpr int kLanes = 4;
   static constexpr uint64_t kLargeLaunchBytes = 4096ull << 20;  // of traffic (bytes x buffers) per launch
   hipStream_t lanes_[kNumKinds][kLanes] = {};
   uint32_t lane_cursor_[kNumKinds] = {};
