@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--window", type=int, default=32, help="config5: operations per window")
     ap.add_argument("--depth", type=int, default=2, help="config5: windows in flight (window x depth <= 64)")
     ap.add_argument("--chunk-bytes", type=int, default=0, help="pin the kernels' chunk size (0 = chosen per launch)")
+    ap.add_argument("--mailbox", type=int, default=0, choices=[0, 1],
+                    help="1 = small flushes go to the resident mailbox kernel instead of being launched")
+    ap.add_argument("--mailbox-workers", type=int, default=0, help="workgroups of the resident kernel (0 = the library's default)")
     ap.add_argument("--reduce-lds", type=int, default=0, help="config3: 1 = LDS-staged all-reduce kernel")
     ap.add_argument("--c3-depth", type=int, default=3, help="config3: iterations in flight (each on input sets of its own)")
     ap.add_argument("--coll-launches", type=int, default=200, help="collectives: timed launches per operation")
@@ -1207,6 +1210,9 @@ def main():
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
     mw.mw_config_set("chunk_bytes", args.chunk_bytes)
+    mw.mw_config_set("mailbox", args.mailbox)
+    if args.mailbox_workers:
+        mw.mw_config_set("mailbox_workers", args.mailbox_workers)
     if args.workload == "config2":
         return main_config2(args, torch, mw, dev)
     mw.mw_init(0, 64)
@@ -1231,6 +1237,7 @@ def main():
            "warmup": args.warmup, "ms_per_step": res.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "f32" if args.workload == "config3" else "u8", "data": "synthetic"}
     out.update(res)
+    out["config"]["mailbox"] = args.mailbox
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_of(args)
     print(json.dumps(out))

@@ -252,9 +252,20 @@ int mw_pending_ops(void);
 /* Poll n handles at once: states[i] = mw_poll(handles[i]).  Returns the number not yet terminal. */
 int mw_poll_many(const mw_handle* handles, int n, int* states);
 
-/* Tunables, to be set between mw_init and the first post.  key: "chunk_bytes" (power of two,
- * 4096..4194304; 0 = choose per launch), "ring_depth" (1..256 slots per world, default 128; before mw_init), "reduce_lds"
- * (0/1: stage all-reduce tiles through LDS).  MW_EINVAL for unknown keys or bad values. */
+/* Tunables.  key: "chunk_bytes" (power of two, 4096..4194304; 0 = choose per launch), "reduce_lds" (0/1: stage
+ * all-reduce tiles through LDS), "mailbox" (0/1, see below) -- these three may be set at any time; "ring_depth" (1..256
+ * slots per world, default 128), "max_rings", "handle_capacity", "mailbox_workers" (1..1023, default 255) -- only before
+ * mw_init.  MW_EINVAL for unknown keys or bad values.
+ *
+ * "mailbox" = 1 turns on the resident mailbox kernel: a flush whose operations have final buffers (no busy caller
+ * stream) and move at most 64 MiB together is not launched but written as descriptors into a queue in device memory
+ * that a resident kernel serves (one leader that admits descriptors and decides when the kernel ends, and
+ * mailbox_workers workgroups that move the data), so a small operation does not pay a kernel launch (Sec. 3.2 / 3.3:
+ * a worker busy-waits on its operation, so that latency is what it sees).  Results, completion and polling are
+ * the same as for launched operations.  The kernel is started on demand and never waited for; it ends by itself
+ * when the host asks (a larger flush wants the whole chip; mw_shutdown), after 300 us without work, and after 100 ms
+ * at the latest; operations that arrive just as it ends are served by the next one, which the following mw_flush or
+ * mw_poll starts.  Off by default. */
 int mw_config_set(const char* key, long value);
 long mw_config_get(const char* key);
 
@@ -282,6 +293,9 @@ int mw_profile_read(int kind, uint64_t* launches, double* total_ms, uint64_t* op
  * mw_debug_arena_hash returns an FNV-1a hash of every ring byte NOT belonging to `except_world`
  * (pass -1 to hash everything) so that tests can show a teardown touched nothing else. */
 long mw_debug_ring_read(int world_id, void* out, size_t cap);
+/* State of the resident mailbox kernel: epoch = how many have been started, open = 1 while the latest has not closed,
+ * tail = descriptors queued so far. */
+int mw_debug_mailbox(uint32_t* epoch, uint32_t* open, uint32_t* tail);
 int mw_debug_arena_hash(int except_world, uint64_t* hash);
 
 #ifdef __cplusplus

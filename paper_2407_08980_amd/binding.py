@@ -31,7 +31,7 @@ SYMBOLS = [
     "mw_config_set", "mw_config_get", "mw_handle_capacity", "mw_last_hip_error", "mw_strerror",
     "mw_profile_enable", "mw_profile_read", "mw_debug_ring_read", "mw_debug_arena_hash", "mw_heartbeat",
     "mw_heartbeat_at", "mw_watchdog_start", "mw_watchdog_stop", "mw_watchdog_check_at", "mw_worker_state",
-    "mw_heartbeat_epoch", "mw_build_id", "mw_post_many_noalloc",
+    "mw_heartbeat_epoch", "mw_build_id", "mw_post_many_noalloc", "mw_debug_mailbox",
 ]
 
 
@@ -91,6 +91,8 @@ def declare(lib):
     lib.mw_debug_ring_read.argtypes = [i, vp, sz]
     lib.mw_debug_ring_read.restype = C.c_long
     lib.mw_debug_arena_hash.argtypes = [i, u64p]
+    u32p = C.POINTER(C.c_uint32)
+    lib.mw_debug_mailbox.argtypes = [u32p, u32p, u32p]
     lib.mw_heartbeat.argtypes = [i]
     lib.mw_heartbeat_at.argtypes = [i, C.c_double]
     lib.mw_watchdog_start.argtypes = [C.c_double, C.c_double]
@@ -371,3 +373,10 @@ def mw_debug_arena_hash(except_world=-1):
     h = C.c_uint64(0)
     _ck(lib().mw_debug_arena_hash(except_world, C.byref(h)), "mw_debug_arena_hash")
     return h.value
+
+
+def mw_debug_mailbox():
+    """(epoch, open, tail) of the resident mailbox kernel."""
+    e, o, t = C.c_uint32(0), C.c_uint32(0), C.c_uint32(0)
+    _ck(lib().mw_debug_mailbox(C.byref(e), C.byref(o), C.byref(t)), "mw_debug_mailbox")
+    return e.value, o.value, t.value

@@ -21,6 +21,7 @@
 // cache policies through hardware bounds-checked windows, no matrix instructions.
 
 #include <hip/hip_runtime.h>
+#include <immintrin.h>
 
 #include <algorithm>
 #include <cstdio>
@@ -29,6 +30,7 @@
 
 #include "../../include/mw.h"
 #include "mw_internal.hpp"
+#include "mw_mailbox.hpp"
 
 // Scratch of the entry point that allocates nothing (mw_post_many_noalloc): ring slots (arrival counter and
 // completion word per operation) followed by the completion words the kernels otherwise write to host-pinned
@@ -38,6 +40,13 @@
 static __device__ __align__(256) unsigned char scratch[MW_NOALLOC_MAX_OPS * (mw::kSlotBytes + 4)];
 constexpr int kMaxHipDevices = 64;
 static unsigned char* g_scratch_ptr[kMaxHipDevices] = {};  // device address of `scratch`, per HIP device
+
+// The mailbox queue lives in fine-grained device memory, which the host writes through the PCIe aperture and the
+// resident kernel polls at HBM speed (measured round trip host -> polling wave -> host: 2.0-2.1 us whatever the
+// number of polling waves; through host-pinned memory the same round trip is 2.4 us with one poller and 25 us with
+// 256, because every poll crosses the bus).  One block per GPU, allocated at the first mw_init on that GPU and kept
+// until the process ends.
+static mw::mb::HostWritten* g_mailbox_mem[kMaxHipDevices] = {};
 
 namespace mw {
 namespace {
@@ -596,6 +605,167 @@ __global__ __launch_bounds__(kReduceWG) void mw_k_reduce(const CollArgs<CAP> a, 
 }
 
 // ------------------------------------------------------------------------------------------------
+// The mailbox: a resident kernel that serves descriptors the host writes into device memory, so that a small
+// operation does not pay a launch (protocol and its reasons: mw_mailbox.hpp).  Workgroup 0 is the leader (one
+// thread), workgroups 1..W are the workers.  Every loop here ends by itself: the leader when the host asks, when
+// nothing has come for `idle_ticks`, or at `life_ticks` at the latest; a worker when it has served everything up to
+// the leader's closing word, or -- a safety net that no correct run needs -- at its own time limit.
+// ------------------------------------------------------------------------------------------------
+// (the builtin returns a signed int: widen through uint32_t, or a low word with bit 31 set smears into the high word)
+__device__ __forceinline__ uint32_t uniform32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint64_t uniform64(uint64_t v) {
+  return ((uint64_t)uniform32((uint32_t)(v >> 32)) << 32) | (uint64_t)uniform32((uint32_t)v);
+}
+
+// One chunk of one descriptor, by the whole workgroup: what one workgroup of mw_k_copy / mw_k_bcast /
+// mw_k_reduce<false> does for one chunk of one entry, ending with the same completion protocol.
+__device__ __forceinline__ void mailbox_chunk(const mb::Desc* d, uint32_t ci, RingSlot* slots, uint32_t* host_flags) {
+  const uint64_t nbytes = uniform64(d->nbytes);
+  const uint32_t slot = uniform32(d->slot), gen = uniform32(d->gen), nbuf = uniform32(d->nbuf), flags = uniform32(d->flags);
+  const uint32_t kind = uniform32(d->kind), nchunks = uniform32(d->op_chunks), target = uniform32(d->target);
+  const uint64_t chunk = uniform32(d->chunk_bytes);
+  uint64_t buf[kMaxBufs];
+#pragma unroll
+  for (int k = 0; k < kMaxBufs; ++k) buf[k] = uniform64(d->buf[k]);
+  const uint64_t off = (uint64_t)ci * chunk;
+  const uint64_t len = (nbytes - off < chunk) ? nbytes - off : chunk;
+  if (ci == 0 && threadIdx.x == 0 && (flags & 1u)) {  // journal the descriptor into the world's ring
+    SlotDesc* j = &slots[slot].d;
+#pragma unroll
+    for (int k = 0; k < kMaxBufs; ++k) j->buf[k] = buf[k];
+    j->nbytes = nbytes;
+    j->kind = (flags >> 8) & 0xFFu;
+    j->dtype = (flags >> 1) & 0x7Fu;
+    j->nbuf = (flags >> 16) & 0xFFu;
+    j->world_id = d->world_id;
+    j->world_epoch = d->world_epoch;
+    j->gen = gen;
+    j->nchunks = nchunks;
+    j->chunk_bytes = (uint32_t)chunk;
+  }
+  if (kind == mb::kKindCopy) {
+    const rsrc_t dw[1] = {window(buf[1] + off, len)};
+    move_any<kCopyWG, kCopyU, 1>(buf[0] | buf[1], window(buf[0] + off, len), dw, 1, (uint32_t)len);
+  } else if (kind == mb::kKindBcast) {
+    rsrc_t dw[kMaxBufs - 1];
+    uint64_t align = buf[0];
+#pragma unroll
+    for (int k = 0; k < kMaxBufs - 1; ++k) {
+      const bool used = k + 1 < (int)nbuf;
+      dw[k] = window(used ? buf[k + 1] + off : 0, used ? len : 0);
+      align |= used ? buf[k + 1] : 0;
+    }
+    move_any<kCopyWG, kCopyU, kMaxBufs - 1>(align, window(buf[0] + off, len), dw, (int)nbuf - 1, (uint32_t)len);
+  } else {
+    const uint32_t wmask = flags >> 24;
+    const bool bf16 = ((flags >> 1) & 0x7Fu) == MW_BF16;
+    const uint32_t isz = bf16 ? 2 : 4;
+    uint64_t align = 0;
+#pragma unroll
+    for (int k = 0; k < kMaxBufs; ++k) align |= buf[k];
+    rsrc_t w[kMaxBufs];
+#pragma unroll
+    for (int k = 0; k < kMaxBufs; ++k) w[k] = window(k < (int)nbuf ? buf[k] + off : 0, k < (int)nbuf ? len : 0);
+    const uint32_t nelem = (uint32_t)len / isz;
+    uint32_t nvec = 0;
+    if ((align & 15) == 0) {
+      nvec = (uint32_t)len >> 4;
+      if (bf16) reduce_vectors_any<true>(buf, off, (uint32_t)len, (int)nbuf, wmask, nvec);
+      else reduce_vectors_any<false>(buf, off, (uint32_t)len, (int)nbuf, wmask, nvec);
+    }
+    const uint32_t first = nvec * (16 / isz);
+    if (first < nelem) {
+      if (bf16) reduce_scalar<true>(w, (int)nbuf, wmask, first, nelem);
+      else reduce_scalar<false>(w, (int)nbuf, wmask, first, nelem);
+    }
+  }
+  retire_chunk(slots, host_flags, slot, gen, nchunks, target);
+}
+
+constexpr int kMailboxBatch = 64;  // descriptors a worker fetches at a time (16 lanes each, one round trip for all);
+                                  // one wavefront then finds this worker's chunks among them, a lane per descriptor
+static_assert(kMailboxBatch == 64 && kMailboxBatch * 16 <= kCopyWG, "one lane of the first wavefront per descriptor");
+
+__global__ __launch_bounds__(kCopyWG) void mw_k_mailbox(const mb::HostWritten* __restrict__ hw, mb::LeaderWritten* __restrict__ lw,
+                                                        uint64_t* __restrict__ closed_host, uint32_t epoch, uint32_t first,
+                                                        uint32_t n_workers, uint64_t idle_ticks, uint64_t life_ticks,
+                                                        RingSlot* __restrict__ slots, uint32_t* __restrict__ host_flags) {
+  if (blockIdx.x == 0) {  // ---- the leader: the only reader of the doorbell, the only one who admits and closes
+    if (threadIdx.x != 0) return;
+    uint32_t go = first - 1;
+    const uint64_t t0 = wall_clock64();
+    uint64_t t_last = t0;
+    for (;;) {
+      // doorbell and stop word in one 8-byte load, past every cache: the host writes them through the PCIe aperture
+      const uint64_t w = __hip_atomic_load(reinterpret_cast<const uint64_t*>(&hw->tail), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      const uint32_t tail = (uint32_t)w, stop = (uint32_t)(w >> 32);
+      const uint64_t now = wall_clock64();
+      if (tail != go && mb::before(go, tail) && tail - first < mb::kEpochTickets) {
+        go = tail;
+        __hip_atomic_store(&lw->admit, mb::make_admit(go, 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        t_last = now;
+        continue;
+      }
+      if (stop == epoch || now - t_last > idle_ticks || now - t0 > life_ticks) {
+        __hip_atomic_store(&lw->admit, mb::make_admit(go, epoch), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0);  // the workers' closing word is out before the host hears of it
+        __hip_atomic_store(closed_host, mb::make_closed(epoch, go), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        return;
+      }
+    }
+  }
+  // ---- a worker
+  __shared__ uint64_t s_admit;
+  __shared__ uint64_t s_mine;                 // which descriptors of the batch hold chunks of mine
+  __shared__ uint32_t s_c0[kMailboxBatch];    // ... and my first chunk of each
+  __shared__ __align__(16) mb::Desc s_desc[kMailboxBatch];
+  const uint32_t me = blockIdx.x - 1;
+  uint32_t next = first;
+  const uint64_t t0 = wall_clock64();
+  const uint64_t my_life = life_ticks + life_ticks / 2 + 50000000ull;  // the leader's life and half a second more
+  for (;;) {
+    if (threadIdx.x == 0) s_admit = __hip_atomic_load(&lw->admit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint64_t a = s_admit;
+    __syncthreads();  // everybody has read it before thread 0 overwrites it in the next round
+    const uint32_t go = (uint32_t)a;
+    const bool closing = mb::closing_epoch(a) == epoch;
+    while (mb::before(next - 1, go)) {
+      const uint32_t batch = go - next + 1 < (uint32_t)kMailboxBatch ? go - next + 1 : (uint32_t)kMailboxBatch;
+      if (threadIdx.x < batch * 16) {  // 16 lanes x 8 bytes per descriptor, past every cache (host-written memory)
+        const uint32_t b = threadIdx.x / 16, k = threadIdx.x % 16;
+        const uint64_t* src = reinterpret_cast<const uint64_t*>(&hw->q[(next + b) % mb::kQueueDepth]) + k;
+        reinterpret_cast<uint64_t*>(&s_desc[b])[k] = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      }
+      __syncthreads();
+      if (threadIdx.x < 64) {  // the first wavefront: lane b looks at descriptor b
+        bool mine = false;
+        if (threadIdx.x < batch) {
+          // my chunks of it: owner(start, c, W) == me  <=>  c = (me - start) mod W, then every W-th
+          const uint32_t c0 = (me + n_workers - s_desc[threadIdx.x].start % n_workers) % n_workers;
+          s_c0[threadIdx.x] = c0;
+          mine = c0 < s_desc[threadIdx.x].n_chunks;
+        }
+        const uint64_t m = __ballot(mine);
+        if (threadIdx.x == 0) s_mine = m;
+      }
+      __syncthreads();
+      uint64_t mine = uniform64(s_mine);
+      while (mine) {
+        const uint32_t b = (uint32_t)__builtin_ctzll(mine);
+        mine &= mine - 1;
+        const uint32_t n_chunks = uniform32(s_desc[b].n_chunks);
+        for (uint32_t c = uniform32(s_c0[b]); c < n_chunks; c += n_workers) mailbox_chunk(&s_desc[b], c, slots, host_flags);
+      }
+      __syncthreads();  // the batch is overwritten next
+      next += batch;
+    }
+    if (closing && next - 1 == go) return;
+    if (wall_clock64() - t0 > my_life) return;  // safety net
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // K5: world marker
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void mw_k_mark(RingHeader* __restrict__ dst, const RingHeader h) {
@@ -624,6 +794,7 @@ class HipDevice : public Device {
   void shutdown() override {
     if (!ready_) return;
     (void)hipSetDevice(dev_);
+    if (mb_hw_) mb_.stop();        // the resident kernel closes within microseconds of the stop word
     (void)hipDeviceSynchronize();  // operations behind a busy caller stream run on that stream
     release();
   }
@@ -631,6 +802,9 @@ class HipDevice : public Device {
   void set_config(const DeviceConfig& cfg) override {
     cfg_.chunk_bytes = cfg.chunk_bytes;
     cfg_.reduce_lds = cfg.reduce_lds;
+    if (cfg_.mailbox && !cfg.mailbox) mb_.stop();
+    cfg_.mailbox = cfg.mailbox;
+    cfg_.mailbox_workers = std::min(1023u, std::max(1u, cfg.mailbox_workers));
   }
 
   int launch(const LaunchOp* ops, const OpDeps* deps, int n, uint8_t* launched) override {
@@ -746,6 +920,10 @@ class HipDevice : public Device {
 
   int sync() override {
     if (chk(hipSetDevice(dev_))) return MW_EHIP;
+    if (mb_hw_) {  // what is queued for the resident kernel is served, then it closes
+      if (mb_.attend() != 0) return MW_EHIP;
+      mb_.stop();
+    }
     if (chk(hipDeviceSynchronize())) return MW_EHIP;  // the lanes, and the caller streams operations were put on
     return MW_OK;
   }
@@ -837,6 +1015,27 @@ class HipDevice : public Device {
       if (hip_device < kMaxHipDevices) g_scratch_ptr[hip_device] = ptr;
       static_base_ = ptr;
     }
+    // The mailbox: queue (process-lifetime, fine-grained), leader's word, closing word, stream.  A GPU that cannot
+    // give host-writable device memory simply has no mailbox: every flush is launched.
+    cfg_.mailbox_workers = std::min(1023u, std::max(1u, cfg.mailbox_workers));
+    mb_.reset();
+    if (hip_device < kMaxHipDevices) {
+      if (!g_mailbox_mem[hip_device]) {
+        void* p = nullptr;
+        if (hipExtMallocWithFlags(&p, sizeof(mb::HostWritten), hipDeviceMallocFinegrained) == hipSuccess) g_mailbox_mem[hip_device] = static_cast<mb::HostWritten*>(p);
+        else (void)hipGetLastError();
+      }
+      mb_hw_ = g_mailbox_mem[hip_device];
+    }
+    if (mb_hw_) {
+      if (chk(hipMemset(mb_hw_, 0, 128))) return MW_EHIP;  // doorbell and stop word
+      if (chk(hipMalloc(reinterpret_cast<void**>(&mb_lw_), sizeof(mb::LeaderWritten))) || chk(hipMemset(mb_lw_, 0, sizeof(mb::LeaderWritten)))) return MW_EHIP;
+      if (chk(hipHostMalloc(reinterpret_cast<void**>(&mb_closed_), 64, hipHostMallocMapped | hipHostMallocCoherent))) return MW_EHIP;
+      *mb_closed_ = 0;
+      if (chk(hipHostGetDevicePointer(reinterpret_cast<void**>(&mb_closed_dev_), mb_closed_, 0))) return MW_EHIP;
+      if (chk(hipStreamCreateWithFlags(&mb_stream_, hipStreamNonBlocking))) return MW_EHIP;
+    }
+    mb_descs_.reserve(512);
     // Host tables sized once, so that launching never grows them (the no-allocation entry point relies on it).
     ents_.reserve(512);
     one_.reserve(64);
@@ -870,6 +1069,13 @@ class HipDevice : public Device {
       }
     if (ctl_) (void)hipStreamDestroy(ctl_);
     ctl_ = nullptr;
+    if (mb_stream_) (void)hipStreamDestroy(mb_stream_);
+    mb_stream_ = nullptr;
+    if (mb_lw_) (void)hipFree(mb_lw_);
+    mb_lw_ = nullptr;
+    if (mb_closed_) (void)hipHostFree(mb_closed_);
+    mb_closed_ = nullptr;
+    mb_hw_ = nullptr;  // the queue itself stays with the process
     if (arena_) (void)hipFree(arena_);
     arena_ = nullptr;
     if (flags_host_) (void)hipHostFree(flags_host_);
@@ -1013,14 +1219,27 @@ class HipDevice : public Device {
 
   // The operations of the dependency-free group (-1), on the library's lanes.
   int launch_group(const LaunchOp* ops, int n, int group) {
+    via_mailbox_ = false;
     if (group < 0) {
       // Each kernel kind has its own streams so that a copy, a broadcast and an all-reduce launch of one
       // flush overlap.
       uint64_t bytes[kNumKinds] = {};
+      uint32_t n_mine = 0;
       for (int i = 0; i < n; ++i) {  // traffic: every buffer once, (all-)reduce reads and writes them
         if (group_of_[(size_t)i] >= 0) continue;
         const uint32_t k = kernel_of(ops[i].kind);
         bytes[k] += ops[i].nbytes * ops[i].nbuf * (k == kReduce ? 2 : 1);
+        n_mine += 1;
+      }
+      if (cfg_.mailbox && mb_hw_ && n_mine) {
+        // A small flush goes to the resident kernel: no launch.  A larger one wants the whole chip: the resident
+        // kernel is asked to close (it does within a microsecond or two; nobody waits for it).
+        const uint64_t traffic = bytes[kCopy] + bytes[kBcast] + bytes[kReduce];
+        if (traffic <= kMailboxMaxTraffic && mb_.room() >= kMaxOpBufs * n_mine) {
+          via_mailbox_ = true;
+        } else {
+          mb_.stop();
+        }
       }
       for (uint32_t k = 0; k < kNumKinds; ++k) {
         if (!bytes[k]) {
@@ -1085,6 +1304,7 @@ class HipDevice : public Device {
       chunks += chunks_[(size_t)i];
     }
     if (chunks == 0 || chunks > 0x7FFFFFFFull) return fail_inval();
+    if (via_mailbox_) return mailbox_entries(kind);
     // Per operation: its chunk count, and the arrival count at which it is complete -- the slot's running total
     // (counts_) plus its chunks.  An operation of one chunk does not touch the counter.
     op_chunks_.resize((size_t)n);
@@ -1188,6 +1408,97 @@ class HipDevice : public Device {
       hipLaunchKernelGGL((mw_k_reduce<false, CAP>), dim3(at), dim3(kReduceWG), 0, data_[kind], a, cur_slots_, cur_flags_);
     }
   }
+
+  // The gathered entries (ents_, with chunks_ / chunk_bytes_ filled in) as descriptors for the resident kernel.
+  int mailbox_entries(uint32_t kind) {
+    const int n = (int)ents_.size();
+    mb_descs_.resize((size_t)n);
+    for (int i = 0; i < n;) {
+      int j = i;
+      uint32_t sum = 0;
+      while (j < n && ents_[(size_t)j].group == ents_[(size_t)i].group) sum += chunks_[(size_t)j++];
+      const uint32_t target = counts_[ents_[(size_t)i].slot] + (sum > 1 ? sum : 0);
+      uint32_t before = 0;
+      for (int k = i; k < j; ++k) {
+        const Ent& e = ents_[(size_t)k];
+        mb::Desc& d = mb_descs_[(size_t)k];
+        std::memset(&d, 0, sizeof(d));
+        for (int b = 0; b < kMaxBufs; ++b) d.buf[b] = e.buf[b];
+        d.nbytes = e.nbytes;
+        d.slot = e.slot;
+        d.gen = e.gen;
+        d.nbuf = e.nbuf;
+        d.chunk_bytes = chunk_bytes_[(size_t)k];
+        d.world_id = e.world_id;
+        d.world_epoch = e.world_epoch;
+        d.op_chunks = sum;
+        d.flags = e.flags;
+        d.target = target;
+        d.kind = kind == kCopy ? mb::kKindCopy : kind == kBcast ? mb::kKindBcast : mb::kKindReduce;
+        d.first_chunk = before;
+        d.n_chunks = chunks_[(size_t)k];
+        before += chunks_[(size_t)k];
+      }
+      i = j;
+    }
+    uint32_t first_ticket = 0;
+    int rc = mb_.submit(mb_descs_.data(), (uint32_t)n, &first_ticket);
+    // The descriptors are queued whether or not the kernel could be started (attend() tries again at the next poll).
+    for (int i = 0; i < n; ++i) {
+      const Ent& e = ents_[(size_t)i];
+      counts_[e.slot] = mb_descs_[(size_t)i].target;
+      launched_[e.group] = 1;
+    }
+    ents_.clear();
+    return rc == 0 ? MW_OK : MW_EHIP;
+  }
+
+ public:
+  // ---- what mb::MailboxHost needs of the device (its Port)
+  void write_desc(uint32_t index, const mb::Desc& d) {
+    // write-combined memory: whole 16-byte stores, no read-modify-write
+    const __m128i* src = reinterpret_cast<const __m128i*>(&d);
+    __m128i* dst = reinterpret_cast<__m128i*>(&mb_hw_->q[index]);
+    for (int k = 0; k < (int)(sizeof(mb::Desc) / 16); ++k) _mm_stream_si128(dst + k, _mm_loadu_si128(src + k));
+  }
+  void ring(uint32_t tail) {
+    _mm_sfence();  // the descriptors leave the core's write-combining buffers before the doorbell does
+    *reinterpret_cast<volatile uint32_t*>(&mb_hw_->tail) = tail;
+    _mm_sfence();
+  }
+  void ask_stop(uint32_t epoch) {
+    *reinterpret_cast<volatile uint32_t*>(&mb_hw_->stop) = epoch;
+    _mm_sfence();
+  }
+  uint64_t closed() { return __atomic_load_n(mb_closed_, __ATOMIC_ACQUIRE); }
+  int launch(uint32_t epoch, uint32_t first) {
+    if (chk(hipSetDevice(dev_))) return MW_EHIP;
+    hipLaunchKernelGGL(mw_k_mailbox, dim3(cfg_.mailbox_workers + 1), dim3(kCopyWG), 0, mb_stream_, mb_hw_, mb_lw_, mb_closed_dev_, epoch,
+                       first, cfg_.mailbox_workers, kMailboxIdleTicks, kMailboxLifeTicks, slots_, flags_dev_);
+    return chk(hipGetLastError()) ? MW_EHIP : MW_OK;
+  }
+  bool needs_attention() override { return mb_hw_ && mb_.needs_attention(); }
+  int attend() override { return mb_hw_ ? (mb_.attend() == 0 ? MW_OK : MW_EHIP) : MW_OK; }
+  void mailbox_state(uint32_t* epoch, uint32_t* open, uint32_t* tail) override {
+    *epoch = mb_.epoch();
+    *open = mb_hw_ && mb_.running() ? 1u : 0u;
+    *tail = mb_.tail();
+  }
+
+ private:
+  // A flush of at most this much traffic goes to the mailbox (the all-reduce iteration of the tensor-parallel
+  // workload is 36 MiB); above it the launch overhead no longer matters and the whole chip is wanted.
+  static constexpr uint64_t kMailboxMaxTraffic = 64ull << 20;
+  // wall_clock64() ticks at 100 MHz: the resident kernel closes after 300 us without work and lives 100 ms at most
+  static constexpr uint64_t kMailboxIdleTicks = 30000, kMailboxLifeTicks = 10000000;
+  mb::HostWritten* mb_hw_ = nullptr;         // the queue (fine-grained device memory, host-writable)
+  mb::LeaderWritten* mb_lw_ = nullptr;       // the leader's word (device memory)
+  uint64_t* mb_closed_ = nullptr;            // what the last leader to close left (host-pinned) ...
+  uint64_t* mb_closed_dev_ = nullptr;        // ... and its device address
+  hipStream_t mb_stream_ = nullptr;          // resident kernels run one after the other on it
+  mb::MailboxHost<HipDevice> mb_{this};
+  std::vector<mb::Desc> mb_descs_;
+  bool via_mailbox_ = false;                 // the current launch_group() call hands its entries to the mailbox
 
   int fail_inval() {
     last_err_ = (int)hipErrorInvalidValue;

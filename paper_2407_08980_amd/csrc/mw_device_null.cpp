@@ -74,6 +74,9 @@ class NullDevice : public Device {
     for (int i = 0; i < n; ++i) st_.log.push_back(Recorded{ops[i], id});  // complete by stream order: never pending
     return MW_OK;
   }
+  bool needs_attention() override { return false; }
+  int attend() override { return MW_OK; }
+  void mailbox_state(uint32_t* epoch, uint32_t* open, uint32_t* tail) override { *epoch = *open = *tail = 0; }
   int mark_world(uint32_t ring_index, const RingHeader& h) override {
     std::lock_guard<std::mutex> g(st_.mu);
     st_.headers[ring_index] = h;

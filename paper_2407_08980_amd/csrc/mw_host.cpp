@@ -164,6 +164,7 @@ std::mutex g_wd_mu;  // guards g_wd_thread / g_wd_running
 std::atomic<bool> g_wd_stop{false};
 bool g_wd_running = false;
 long g_cfg_chunk = 0, g_cfg_depth = kDefaultRingDepth, g_cfg_lds = 0, g_cfg_rings = 1024, g_cfg_handles = 1 << 20;
+long g_cfg_mailbox = 0, g_cfg_mailbox_workers = 255;
 
 inline mw_handle make_handle(uint32_t slot, uint32_t gen) { return ((uint64_t)gen << 32) | slot; }
 
@@ -261,6 +262,10 @@ void retire_one(Context& c, uint32_t opi) {
 
 // ---- launching ---------------------------------------------------------------------------------
 int flush_locked(Context& c) {
+  if (c.dev->needs_attention()) {  // operations queued for the resident kernel that closed as they came in
+    int rc = c.dev->attend();
+    if (rc != MW_OK) return rc;
+  }
   if (c.ready.empty()) return MW_OK;
   c.launch_buf.clear();
   c.deps_buf.clear();
@@ -586,7 +591,11 @@ inline bool poll_fast(Context& c, mw_handle h, int* state) {
     *state = st;
     return true;
   }
-  if (op == kNone || (fs != kNone && c.dev->flag(fs) != fg)) {
+  if (op == kNone) {
+    *state = MW_PENDING;
+    return true;
+  }
+  if (fs != kNone && c.dev->flag(fs) != fg && !c.dev->needs_attention()) {
     *state = MW_PENDING;
     return true;
   }
@@ -611,6 +620,10 @@ int poll_locked(Context& c, mw_handle h) {
     retire_one(c, opi);
     return MW_DONE;
   }
+  if (c.dev->needs_attention()) {  // it may sit in the resident kernel's queue with no kernel open: start one
+    int rc = c.dev->attend();
+    if (rc != MW_OK) return rc;
+  }
   return MW_PENDING;
 }
 
@@ -632,6 +645,8 @@ int mw_init(int hip_device, int n_workers) {
   c->cfg.total_slots = c->max_rings * c->ring_depth;
   c->cfg.chunk_bytes = (uint32_t)g_cfg_chunk;
   c->cfg.reduce_lds = (uint32_t)g_cfg_lds;
+  c->cfg.mailbox = (uint32_t)g_cfg_mailbox;
+  c->cfg.mailbox_workers = (uint32_t)g_cfg_mailbox_workers;
   c->dev.reset(make_device());
   int rc = c->dev->init(hip_device, c->cfg);
   if (rc != MW_OK) return rc;
@@ -1107,8 +1122,22 @@ int mw_config_set(const char* key, long value) {
     }
     return MW_OK;
   }
+  if (!std::strcmp(key, "mailbox")) {
+    if (value != 0 && value != 1) return MW_EINVAL;
+    g_cfg_mailbox = value;
+    if (live) {
+      g_ctx->cfg.mailbox = (uint32_t)value;
+      g_ctx->dev->set_config(g_ctx->cfg);
+    }
+    return MW_OK;
+  }
   // geometry: only before mw_init
   if (live) return MW_EINVAL;
+  if (!std::strcmp(key, "mailbox_workers")) {
+    if (value < 1 || value > 1023) return MW_EINVAL;
+    g_cfg_mailbox_workers = value;
+    return MW_OK;
+  }
   if (!std::strcmp(key, "ring_depth")) {
     if (value < 1 || value > kMaxRingDepth) return MW_EINVAL;
     g_cfg_depth = value;
@@ -1132,6 +1161,8 @@ long mw_config_get(const char* key) {
   if (!key) return MW_EINVAL;
   if (!std::strcmp(key, "chunk_bytes")) return g_cfg_chunk;
   if (!std::strcmp(key, "reduce_lds")) return g_cfg_lds;
+  if (!std::strcmp(key, "mailbox")) return g_cfg_mailbox;
+  if (!std::strcmp(key, "mailbox_workers")) return g_cfg_mailbox_workers;
   if (!std::strcmp(key, "ring_depth")) return g_cfg_depth;
   if (!std::strcmp(key, "max_rings")) return g_cfg_rings;
   if (!std::strcmp(key, "handle_capacity")) return g_cfg_handles;
@@ -1180,6 +1211,14 @@ int mw_profile_read(int kind, uint64_t* launches, double* total_ms, uint64_t* op
   if (!g_ctx) return MW_ENOTINIT;
   if (kind < 0 || kind >= (int)kNumKinds || !launches || !total_ms || !op_bytes) return MW_EINVAL;
   return g_ctx->dev->profile_read(kind, launches, total_ms, op_bytes);
+}
+
+int mw_debug_mailbox(uint32_t* epoch, uint32_t* open, uint32_t* tail) {
+  std::lock_guard<std::mutex> g(g_lock);
+  if (!g_ctx) return MW_ENOTINIT;
+  if (!epoch || !open || !tail) return MW_EINVAL;
+  g_ctx->dev->mailbox_state(epoch, open, tail);
+  return MW_OK;
 }
 
 long mw_debug_ring_read(int world_id, void* out, size_t cap) {

@@ -106,6 +106,8 @@ struct DeviceConfig {
   uint32_t total_rings;   // ring headers in the arena
   uint32_t chunk_bytes;   // 0 = choose per launch
   uint32_t reduce_lds;    // stage all-reduce tiles through LDS
+  uint32_t mailbox;       // serve small flushes through the resident mailbox kernel instead of launching
+  uint32_t mailbox_workers;  // workgroups of the resident kernel that move data (1..1023)
 };
 
 class Device {
@@ -123,6 +125,12 @@ class Device {
   // Enqueue `n` <= MW_NOALLOC_MAX_OPS operations on the caller's stream with their completion state in the static
   // device scratch (slot = index of the operation); allocates nothing, publishes nothing to the host.
   virtual int launch_static(const LaunchOp* ops, int n, void* stream) = 0;
+  // The mailbox (resident kernel): true when operations wait in its queue and no kernel is open to serve them
+  // (it closed for lack of work just as they came in); cheap and callable without the lock.  attend() starts the
+  // next kernel then.  mailbox_state: epoch of the last kernel started, whether it is still open, last ticket queued.
+  virtual bool needs_attention() = 0;
+  virtual int attend() = 0;
+  virtual void mailbox_state(uint32_t* epoch, uint32_t* open, uint32_t* tail) = 0;
   // Write a ring header (world create / abort marker).  Asynchronous, on the library's stream.
   virtual int mark_world(uint32_t ring_index, const RingHeader& h) = 0;
   // Host-visible completion word of a slot (acquire load of the pinned mirror).

@@ -83,13 +83,16 @@ def wait_all(outstanding, status, timeout_s=120.0):
             raise TimeoutError(f"{mw.mw_pending_ops()} operations did not complete within {timeout_s} s")
 
 
-def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn=None, on_init=None, on_exit=None):
+def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn=None, on_init=None, on_exit=None,
+              settle=False):
     """Execute `trace`; returns a DeviceRun.  mw_init / mw_shutdown bracket the run.
 
     check_fn(idx, op, bufs), if given, is called at every "check" op with the dict of live device
     tensors (buffer id -> uint8 tensor) once everything outstanding has completed; use it with
     snapshots=False to verify large buffers on the device instead of copying them out.
-    on_init() / on_exit() run right after mw_init and right before mw_shutdown (e.g. to run the watchdog)."""
+    on_init() / on_exit() run right after mw_init and right before mw_shutdown (e.g. to run the watchdog).
+    settle=True finishes every buffer initialisation before the operation that uses it is posted, so that the
+    operation finds its caller stream idle and depends on nothing (the resident mailbox kernel serves only such)."""
     dev = torch.device("cuda", device)
     torch.cuda.set_device(dev)
     pools = DevicePools(host_pools, dev)
@@ -125,8 +128,11 @@ def run_trace(trace, host_pools, materialize, device=0, snapshots=True, check_fn
                 p2 = t2.data_ptr() if t2 is not None else None
                 s = streams[op.stream]
                 if touched:  # make every caller stream see the initialised bytes
-                    for st in streams:
-                        st.wait_stream(cur)
+                    if settle:
+                        torch.cuda.synchronize(dev)
+                    else:
+                        for st in streams:
+                            st.wait_stream(cur)
                     touched = False
                 dt = mw.DTYPES[op.dtype]
                 try:

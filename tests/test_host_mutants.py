@@ -38,7 +38,7 @@ MUTANTS = [
     ("watchdog takes a report exactly as old as the timeout for a miss", "!(now - c.last_beat[k] > timeout)", "!(now - c.last_beat[k] >= timeout)"),
     ("watchdog aborts the worlds of every watched worker", "    for (uint32_t wi : c.worlds_of_worker[k]) abort_world_locked(c, *c.worlds[wi]);",
      "    for (size_t q = 0; q < c.beating.size(); ++q) if (c.beating[q]) for (uint32_t wi : c.worlds_of_worker[q]) abort_world_locked(c, *c.worlds[wi]);"),
-    ("a poll without the lock never looks at the completion word", "(fs != kNone && c.dev->flag(fs) != fg)", "(fs != kNone)"),
+    ("a poll without the lock never looks at the completion word", "(fs != kNone && c.dev->flag(fs) != fg && !c.dev->needs_attention())", "(fs != kNone && !c.dev->needs_attention())"),
     ("a poll without the lock takes a launched operation for a complete one", "  if (st != MW_PENDING) {\n    *state = st;\n    return true;\n  }\n  if (op == kNone",
      "  if (st != MW_PENDING || fs != kNone) {\n    *state = fs != kNone ? MW_DONE : st;\n    return true;\n  }\n  if (op == kNone"),
     ("the allocation-free variant pairs a side with a side of its own kind", "posts[j].kind == 1 - p.kind", "posts[j].kind == p.kind"),
