@@ -52,8 +52,8 @@ def parse():
     ap.add_argument("--window", type=int, default=32, help="config5: operations per window")
     ap.add_argument("--depth", type=int, default=2, help="config5: windows in flight (window x depth <= 64)")
     ap.add_argument("--chunk-bytes", type=int, default=0, help="pin the kernels' chunk size (0 = chosen per launch)")
-    ap.add_argument("--mailbox", type=int, default=0, choices=[0, 1],
-                    help="1 = small flushes go to the resident mailbox kernel instead of being launched")
+    ap.add_argument("--mailbox", type=int, default=1, choices=[0, 1],
+                    help="1 (the library's default) = small flushes go to the resident mailbox kernel, 0 = every flush is launched")
     ap.add_argument("--mailbox-workers", type=int, default=0, help="workgroups of the resident kernel (0 = the library's default)")
     ap.add_argument("--reduce-lds", type=int, default=0, help="config3: 1 = LDS-staged all-reduce kernel")
     ap.add_argument("--c3-depth", type=int, default=3, help="config3: iterations in flight (each on input sets of its own)")
@@ -322,6 +322,21 @@ def main_config2(args, torch, mw, dev):
 # --------------------------------------------------------------------------------------------------
 # the other workloads (timing only; their parity is covered by tests/)
 # --------------------------------------------------------------------------------------------------
+class launched_only:
+    """Within the block every flush is launched (the resident mailbox kernel is switched off): the event records that
+    time kernels see launches only."""
+
+    def __init__(self, mw):
+        self.mw = mw
+
+    def __enter__(self):
+        self.before = self.mw.mw_config_get("mailbox")
+        self.mw.mw_config_set("mailbox", 0)
+
+    def __exit__(self, *exc):
+        self.mw.mw_config_set("mailbox", self.before)
+
+
 def _profile(mw, kind):
     launches, ms, op_bytes = mw.mw_profile_read(kind)
     return launches, ms, op_bytes
@@ -538,22 +553,34 @@ def run_config3(torch, mw, dev, iters, reps, lds, depth=2):
     multi, single = make(list(range(n_worlds))), make([99] * n_worlds)
     run(multi, 20)
     secs = run(multi, iters)
-    # kernel time from a second pass of the same iterations: at ~10 us per iteration the four event records
-    # per iteration would cost a fifth of the rate if they sat in the timed pass
-    mw.mw_profile_enable(True)
-    mw.mw_profile_read(mw.KIND_REDUCE)
-    secs_profiled = run(multi, iters)
-    launches, kernel_ms, op_bytes = _profile(mw, mw.KIND_REDUCE)
-    mw.mw_profile_enable(False)
+    # kernel time from a second pass of the same iterations, launched (a resident kernel cannot be bracketed by
+    # events): at ~10 us per iteration the four event records per iteration would cost a fifth of the rate if they
+    # sat in the timed pass
+    with launched_only(mw):
+        run(multi, 20)
+        mw.mw_profile_enable(True)
+        mw.mw_profile_read(mw.KIND_REDUCE)
+        secs_profiled = run(multi, iters)
+        launches, kernel_ms, op_bytes = _profile(mw, mw.KIND_REDUCE)
+        mw.mw_profile_enable(False)
     mw_r, sw_r = [], []
     for _ in range(reps):
         sw_r.append(iters * per_iter_bytes / run(single, iters) / 1e9)
         mw_r.append(iters * per_iter_bytes / run(multi, iters) / 1e9)
-    by_depth = {}
     want = depth
-    for depth in (1, 2, 3):  # the same loop with fewer iterations in flight, for the record
-        by_depth[str(depth)] = round(run(multi, iters) / iters * 1e6, 2)
-    depth = want
+
+    def sweep_depth():  # the same loop with fewer iterations in flight, for the record
+        nonlocal depth
+        out = {}
+        for depth in (1, 2, 3):
+            out[str(depth)] = round(run(multi, iters) / iters * 1e6, 2)
+        depth = want
+        return out
+
+    by_depth = sweep_depth()
+    with launched_only(mw):
+        run(multi, 20)
+        by_depth_launched = sweep_depth()
     mean = lambda v: sum(v) / len(v) if v else float("nan")
     value = iters * per_iter_bytes / secs / 1e9
     alg = 2.0 * n_ranks * op_bytes  # n reads + n writes of every payload
@@ -565,7 +592,8 @@ def run_config3(torch, mw, dev, iters, reps, lds, depth=2):
                    "worlds": n_worlds, "ranks": n_ranks, "payload_dtype": "f32", "steps_in_flight": depth,
                    "reduce_lds": lds},
         "us_per_iteration": round(secs / iters * 1e6, 2), "us_per_iteration_by_iterations_in_flight": by_depth,
-        "us_per_iteration_with_kernel_timing": round(secs_profiled / iters * 1e6, 2),
+        "us_per_iteration_by_iterations_in_flight_every_flush_launched": by_depth_launched,
+        "us_per_iteration_launched_with_kernel_timing": round(secs_profiled / iters * 1e6, 2),
         "algorithmic_traffic_GBps": round(2 * n_ranks * value, 1),
         "single_world_GBps": round(mean(sw_r), 2) if reps else None,
         "multi_world_GBps_mean": round(mean(mw_r), 2) if reps else None,
@@ -573,7 +601,8 @@ def run_config3(torch, mw, dev, iters, reps, lds, depth=2):
         "roofline": {"bound": "hbm", "kernel": "mw_k_reduce", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "launches": launches,
                      "avg_launch_ms": round(kernel_ms / max(launches, 1), 5),
-                     "note": "working set fits the 256 MB last-level cache: not an HBM figure"},
+                     "note": "working set fits the 256 MB last-level cache: not an HBM figure; kernel time of the launched "
+                             "form (mailbox off), one launch per iteration"},
     }
 
 
@@ -627,33 +656,44 @@ def run_config1(torch, mw, dev, reps):
         return time.perf_counter() - t0
 
     multi, single = make(False), make(True)
-    for _ in range(5):
-        run(multi), run(single), run_two_in_flight(multi)
-    piped = sorted(run_two_in_flight(multi) for _ in range(max(reps, 1) * 8))
-    mw_t, sw_t = [], []
-    for _ in range(max(reps, 1) * 8):  # interleaved so that clock and cache state are shared
-        sw_t.append(run(single))
-        mw_t.append(run(multi))
-    if not torch.equal(src, dst):
-        raise RuntimeError("config 1: destination differs from source")
-    rt = []
-    for k in range(200):
-        t0 = time.perf_counter()
-        hs = mw.mw_send(k % 2, 1, 0, src[k].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE)
-        hr = mw.mw_recv(k % 2, 1, 0, dst[k].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE)
-        mw.mw_flush()
-        while mw.mw_poll(hr) != mw.MW_DONE:
-            pass
-        rt.append(time.perf_counter() - t0)
-    rt.sort()
-    # kernel time in a pass of its own: the event records would cost a good part of a ~10 us window
-    mw.mw_profile_enable(True)
-    mw.mw_profile_read(mw.KIND_COPY)
-    for _ in range(8):
-        run(multi)
-    launches, kernel_ms, op_bytes = mw.mw_profile_read(mw.KIND_COPY)
-    mw.mw_profile_enable(False)
     mean = lambda v: sum(v) / len(v)
+
+    def round_trips():
+        rt = []
+        for k in range(200):
+            t0 = time.perf_counter()
+            mw.mw_send(k % 2, 1, 0, src[k].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE)
+            hr = mw.mw_recv(k % 2, 1, 0, dst[k].data_ptr(), count, mw.MW_F32, mw.STREAM_NONE)
+            mw.mw_flush()
+            while mw.mw_poll(hr) != mw.MW_DONE:
+                pass
+            rt.append(time.perf_counter() - t0)
+        rt.sort()
+        return {"median": round(rt[len(rt) // 2] * 1e6, 2), "p10": round(rt[len(rt) // 10] * 1e6, 2),
+                "p90": round(rt[9 * len(rt) // 10] * 1e6, 2)}
+
+    def measure():
+        for _ in range(5):
+            run(multi), run(single), run_two_in_flight(multi)
+        piped = sorted(run_two_in_flight(multi) for _ in range(max(reps, 1) * 8))
+        mw_t, sw_t = [], []
+        for _ in range(max(reps, 1) * 8):  # interleaved so that clock and cache state are shared
+            sw_t.append(run(single))
+            mw_t.append(run(multi))
+        if not torch.equal(src, dst):
+            raise RuntimeError("config 1: destination differs from source")
+        return mw_t, sw_t, piped, round_trips()
+
+    mw_t, sw_t, piped, rt = measure()
+    with launched_only(mw):
+        l_mw_t, l_sw_t, l_piped, l_rt = measure()
+        # kernel time in a pass of its own: the event records would cost a good part of a ~10 us window
+        mw.mw_profile_enable(True)
+        mw.mw_profile_read(mw.KIND_COPY)
+        for _ in range(8):
+            run(multi)
+        launches, kernel_ms, op_bytes = mw.mw_profile_read(mw.KIND_COPY)
+        mw.mw_profile_enable(False)
     secs = mean(mw_t)
     value = n_msgs * count * 4 / secs / 1e9
     return {
@@ -664,13 +704,17 @@ def run_config1(torch, mw, dev, reps):
         "us_per_message_windowed": round(secs / n_msgs * 1e6, 3),
         "messages_per_s": round(n_msgs / secs),
         "us_per_message_two_windows_in_flight": round(piped[len(piped) // 2] / n_msgs * 1e6, 3),
-        "single_message_round_trip_us": {"median": round(rt[len(rt) // 2] * 1e6, 2), "p10": round(rt[len(rt) // 10] * 1e6, 2),
-                                         "p90": round(rt[9 * len(rt) // 10] * 1e6, 2)},
+        "single_message_round_trip_us": rt,
         "single_world_GBps": round(n_msgs * count * 4 / mean(sw_t) / 1e9, 3),
         "loss_vs_single_world_pct": round((1 - mean(sw_t) / mean(mw_t)) * 100, 3),
+        "every_flush_launched": {"us_per_message_windowed": round(mean(l_mw_t) / n_msgs * 1e6, 3),
+                                 "us_per_message_two_windows_in_flight": round(l_piped[len(l_piped) // 2] / n_msgs * 1e6, 3),
+                                 "single_message_round_trip_us": l_rt,
+                                 "loss_vs_single_world_pct": round((1 - mean(l_sw_t) / mean(l_mw_t)) * 100, 3)},
         "roofline": roofline("mw_k_copy", 2 * op_bytes, launches, kernel_ms,
                              note="latency-bound: one launch moves a window of 16 messages of 32 KiB (1 MiB of traffic, 0.13 us at "
-                                  "the HBM peak), the launch itself takes several us; measured in a separate pass with event records"),
+                                  "the HBM peak), the launch itself takes several us; kernel time of the launched form (mailbox "
+                                  "off), measured in a separate pass with event records"),
     }
 
 
@@ -1238,9 +1282,25 @@ def main():
            "vs_baseline": None, "dtype": "f32" if args.workload == "config3" else "u8", "data": "synthetic"}
     out.update(res)
     out["config"]["mailbox"] = args.mailbox
+    if args.workload == "config1":
+        out["single_message_post_to_done_from_c_us"] = pingpong_from_c(8 * 1024 * 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_of(args)
     print(json.dumps(out))
+
+
+def pingpong_from_c(nbytes):
+    """The same single message timed by the package's C program (no interpreter between post and poll): one dict
+    per mode, {"mailbox": 1/0, "post_us", "flush_us", "wait_us", "total_us": {...}}."""
+    import subprocess
+    from paper_2407_08980_amd import build
+
+    if not os.path.exists(build.PINGPONG):
+        return None
+    p = subprocess.run([build.PINGPONG, "--iters", "2000", "--sizes", str(nbytes)], capture_output=True, text=True, timeout=120)
+    if p.returncode != 0:
+        raise RuntimeError("pingpong.bin failed: " + p.stderr[-500:])
+    return [json.loads(line) for line in p.stdout.splitlines() if line.startswith("{")]
 
 
 def cpu_baseline_config4(steps, abort_step):

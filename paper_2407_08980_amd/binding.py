@@ -243,10 +243,20 @@ class PollSet:
         self.n = len(handles)
         self.handles = (C.c_uint64 * self.n)(*handles)
         self.states = (C.c_int * self.n)()
+        self._bind()
+
+    def _bind(self):
+        # pointers made once: converting an array argument on every call costs more than the library's own work
+        self._hp = C.cast(self.handles, C.POINTER(C.c_uint64))
+        self._sp = C.cast(self.states, C.POINTER(C.c_int))
+        self._call = lib().mw_poll_many
 
     def poll(self):
         """Number of handles still pending; self.states holds every state."""
-        return _ck(lib().mw_poll_many(self.handles, self.n, self.states), "mw_poll_many")
+        rc = self._call(self._hp, self.n, self._sp)
+        if rc < 0:
+            raise MwError(rc, "mw_poll_many")
+        return rc
 
 
 class PostBatch:
@@ -262,11 +272,15 @@ class PostBatch:
             d.hip_stream = stream if stream != STREAM_NONE else C.c_void_p(-1).value
         self.handles = (C.c_uint64 * self.n)()
         self.results = (C.c_int * self.n)()
+        self._dp = C.cast(self.descs, C.POINTER(PostDesc))  # pointers made once (see PollSet._bind)
+        self._hp = C.cast(self.handles, C.POINTER(C.c_uint64))
+        self._rp = C.cast(self.results, C.POINTER(C.c_int))
+        self._call = lib().mw_post_many
 
     def post(self, check=True):
-        rc = lib().mw_post_many(self.descs, self.n, self.handles, self.results)
-        if check:
-            _ck(rc, "mw_post_many")
+        rc = self._call(self._dp, self.n, self._hp, self._rp)
+        if check and rc < 0:
+            raise MwError(rc, "mw_post_many")
         return rc
 
     def pollset(self):
@@ -276,6 +290,7 @@ class PostBatch:
         if ps is None:
             ps = PollSet.__new__(PollSet)
             ps.n, ps.handles, ps.states = self.n, self.handles, (C.c_int * self.n)()
+            ps._bind()
             self._pollset = ps
         return ps
 

@@ -3,6 +3,7 @@
   libmw.so            the product: host runtime + HIP kernels for gfx950
   libmw_hostcheck.so  host runtime + a device test double that moves no bytes
                       (used only by the CPU tests of the host state machine)
+  pingpong.bin        post-to-done time of one message through the C ABI (no interpreter in the loop)
 """
 
 from __future__ import annotations
@@ -16,6 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmw.so")
 LIB_HOSTCHECK = os.path.join(HERE, "libmw_hostcheck.so")
 ABI_CHECK = os.path.join(HERE, "abi_check.bin")  # tests/abi_check.cpp: a program that uses the C ABI directly
+PINGPONG = os.path.join(HERE, "pingpong.bin")    # pingpong.cpp: post-to-done time of one message, from C
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 HIP_FLAGS = [
@@ -93,10 +95,17 @@ def build_abi_check():
                  "-L" + HERE, "-lmw", "-Wl,-rpath,$ORIGIN"])
 
 
+def build_pingpong():
+    """The latency tool, linked against the product library beside it."""
+    return _run([HIPCC, "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wno-unused-command-line-argument", "-Wno-unused-result",
+                 os.path.join(HERE, "pingpong.cpp"), "-o", PINGPONG, "-L" + HERE, "-lmw", "-Wl,-rpath,$ORIGIN"])
+
+
 def build_all():
     out = build_product()
     out += build_hostcheck()
     out += build_abi_check()
+    out += build_pingpong()
     return out
 
 

@@ -109,6 +109,7 @@ struct Context {
   std::vector<OpRec> ops;
   std::vector<uint32_t> free_ops;
   std::deque<uint32_t> ready;  // op records waiting for a launch, in match order
+  std::deque<uint32_t> deferred;  // flush_locked's scratch: operations whose ring is full
 
   std::unique_ptr<HandleEnt[]> handles;  // fixed size: entries are read without the lock
   uint32_t n_handles = 0;
@@ -164,7 +165,7 @@ std::mutex g_wd_mu;  // guards g_wd_thread / g_wd_running
 std::atomic<bool> g_wd_stop{false};
 bool g_wd_running = false;
 long g_cfg_chunk = 0, g_cfg_depth = kDefaultRingDepth, g_cfg_lds = 0, g_cfg_rings = 1024, g_cfg_handles = 1 << 20;
-long g_cfg_mailbox = 0, g_cfg_mailbox_workers = 255;
+long g_cfg_mailbox = 1, g_cfg_mailbox_workers = 255;
 
 inline mw_handle make_handle(uint32_t slot, uint32_t gen) { return ((uint64_t)gen << 32) | slot; }
 
@@ -270,7 +271,8 @@ int flush_locked(Context& c) {
   c.launch_buf.clear();
   c.deps_buf.clear();
   c.launched_buf.clear();
-  std::deque<uint32_t> deferred;
+  std::deque<uint32_t>& deferred = c.deferred;  // (a member: building a deque allocates)
+  deferred.clear();
   while (!c.ready.empty()) {
     uint32_t opi = c.ready.front();
     c.ready.pop_front();
@@ -404,6 +406,61 @@ int post_p2p_locked(Context& c, bool is_send, int world_id, int src, int dst, co
 
 inline bool rooted(uint32_t kind) { return kind == opBcast || kind == opReduce || kind == opGather || kind == opScatter; }
 
+// A collective all of whose n ranks have posted: check that the sides agree, then queue it (or complete it on the
+// spot when there is nothing to move).
+int run_collective(Context& c, uint32_t wi, const Coll& f, int n) {
+  bool same = true;
+  for (int r = 1; r < n; ++r) {
+    same &= f.kind[r] == f.kind[0] && f.root[r] == f.root[0] && f.post[r].count == f.post[0].count &&
+            f.post[r].dtype == f.post[0].dtype;
+  }
+  if (!same) {
+    for (int r = 0; r < n; ++r) finish_handle(c, f.post[r].hslot, MW_EMISMATCH);
+    return MW_OK;
+  }
+  const uint32_t k = f.kind[0];
+  const int rt = f.root[0];
+  const bool moves_alone = k == opAllGather || k == opGather || k == opScatter;  // a 1-rank world still copies
+  if (f.post[0].count == 0 || (n == 1 && (!moves_alone || f.post[0].buf == f.post[0].buf2))) {
+    for (int r = 0; r < n; ++r) finish_handle(c, f.post[r].hslot, MW_DONE);
+    return MW_OK;
+  }
+  LaunchOp l{};
+  l.kind = k;
+  l.dtype = f.post[0].dtype;
+  l.nbytes = f.post[0].count * item_size(f.post[0].dtype);
+  l.nbuf = (uint32_t)n;
+  l.root = (uint32_t)rt;
+  switch (k) {
+    case opBcast: {  // root first, then the other ranks ascending
+      int at = 0;
+      l.buf[at++] = f.post[rt].buf;
+      for (int r = 0; r < n; ++r)
+        if (r != rt) l.buf[at++] = f.post[r].buf;
+      break;
+    }
+    case opAllReduce:
+    case opReduce:
+      for (int r = 0; r < n; ++r) l.buf[r] = f.post[r].buf;
+      break;
+    case opAllGather:
+      for (int r = 0; r < n; ++r) {
+        l.buf[r] = f.post[r].buf;
+        l.buf[8 + r] = f.post[r].buf2;
+      }
+      break;
+    case opGather:
+      for (int r = 0; r < n; ++r) l.buf[r] = f.post[r].buf;
+      l.buf[8] = f.post[rt].buf2;
+      break;
+    default:  // opScatter
+      l.buf[0] = f.post[rt].buf;
+      for (int r = 0; r < n; ++r) l.buf[8 + r] = f.post[r].buf2;
+      break;
+  }
+  return enqueue_op(c, wi, l, f.post, n);
+}
+
 // kind is an OpKind other than opCopy.  buf / buf2 by kind:
 //   broadcast, all-reduce, reduce: buf = the rank's tensor
 //   all-gather: buf = source (count), buf2 = destination (n x count)
@@ -444,59 +501,9 @@ int post_coll_locked(Context& c, uint32_t kind, int world_id, int rank, int root
   cl.nposted += 1;
   // A world's collectives run in sequence order, each as soon as all its ranks have posted.
   while (!w.coll.empty() && w.coll.front().nposted == n) {
-    Coll f = w.coll.front();
+    rc = run_collective(c, it->second, w.coll.front(), n);
     w.coll.pop_front();
     w.coll_base += 1;
-    bool same = true;
-    for (int r = 1; r < n; ++r) {
-      same &= f.kind[r] == f.kind[0] && f.root[r] == f.root[0] && f.post[r].count == f.post[0].count &&
-              f.post[r].dtype == f.post[0].dtype;
-    }
-    if (!same) {
-      for (int r = 0; r < n; ++r) finish_handle(c, f.post[r].hslot, MW_EMISMATCH);
-      continue;
-    }
-    const uint32_t k = f.kind[0];
-    const int rt = f.root[0];
-    const bool moves_alone = k == opAllGather || k == opGather || k == opScatter;  // a 1-rank world still copies
-    if (f.post[0].count == 0 || (n == 1 && (!moves_alone || f.post[0].buf == f.post[0].buf2))) {
-      for (int r = 0; r < n; ++r) finish_handle(c, f.post[r].hslot, MW_DONE);
-      continue;
-    }
-    LaunchOp l{};
-    l.kind = k;
-    l.dtype = f.post[0].dtype;
-    l.nbytes = f.post[0].count * item_size(f.post[0].dtype);
-    l.nbuf = (uint32_t)n;
-    l.root = (uint32_t)rt;
-    switch (k) {
-      case opBcast: {  // root first, then the other ranks ascending
-        int at = 0;
-        l.buf[at++] = f.post[rt].buf;
-        for (int r = 0; r < n; ++r)
-          if (r != rt) l.buf[at++] = f.post[r].buf;
-        break;
-      }
-      case opAllReduce:
-      case opReduce:
-        for (int r = 0; r < n; ++r) l.buf[r] = f.post[r].buf;
-        break;
-      case opAllGather:
-        for (int r = 0; r < n; ++r) {
-          l.buf[r] = f.post[r].buf;
-          l.buf[8 + r] = f.post[r].buf2;
-        }
-        break;
-      case opGather:
-        for (int r = 0; r < n; ++r) l.buf[r] = f.post[r].buf;
-        l.buf[8] = f.post[rt].buf2;
-        break;
-      default:  // opScatter
-        l.buf[0] = f.post[rt].buf;
-        for (int r = 0; r < n; ++r) l.buf[8 + r] = f.post[r].buf2;
-        break;
-    }
-    rc = enqueue_op(c, it->second, l, f.post, n);
     if (rc != MW_OK) return rc;
   }
   return MW_OK;

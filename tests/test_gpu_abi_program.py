@@ -25,3 +25,22 @@ def test_header_is_plain_c(tmp_path):
     p = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only", "-I", os.path.join(ROOT, "include"),
                         str(src)], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     assert p.returncode == 0, p.stdout
+
+
+@pytest.mark.gpu
+def test_the_latency_program_moves_the_right_bytes_in_both_modes():
+    """pingpong.bin: single messages through the resident mailbox kernel and launched; it checks the payload itself.
+    The timing is printed, not judged -- except that a message through the mailbox must not take longer than a launched
+    one by more than measurement noise (the mailbox exists to save the launch)."""
+    import json
+
+    from paper_2407_08980_amd import build
+
+    assert os.path.exists(build.PINGPONG), "run `python -m paper_2407_08980_amd.build`"
+    p = subprocess.run([build.PINGPONG, "--iters", "500", "--sizes", "4,4096,32768,40000"], capture_output=True, text=True, timeout=120)
+    assert p.returncode == 0, p.stdout[-1000:] + p.stderr[-1000:]
+    rows = [json.loads(line) for line in p.stdout.splitlines() if line.startswith("{")]
+    assert [(r["bytes"], r["mailbox"]) for r in rows] == [(b, m) for m in (1, 0) for b in (4, 4096, 32768, 40000)]
+    by = {(r["bytes"], r["mailbox"]): r["total_us"]["median"] for r in rows}
+    print(by)
+    assert by[(32768, 1)] < by[(32768, 0)] * 1.1

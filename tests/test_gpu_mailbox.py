@@ -32,9 +32,10 @@ def mailbox(torch):
     from paper_2407_08980_amd import binding
 
     binding.lib()
+    before = binding.mw_config_get("mailbox")
     binding.mw_config_set("mailbox", 1)
     yield binding
-    binding.mw_config_set("mailbox", 0)
+    binding.mw_config_set("mailbox", before)
 
 
 def _both(trace, host_pools):

@@ -27,8 +27,8 @@ MUTANTS = [
     ("root disagreement goes unnoticed", "same &= f.kind[r] == f.kind[0] && f.root[r] == f.root[0] &&", "same &= f.kind[r] == f.kind[0] &&"),
     ("a failed worker breaks every world", "  for (uint32_t wi : c.worlds_of_worker[(size_t)worker_id]) {\n    int r = abort_world_locked(c, *c.worlds[wi]);",
      "  for (uint32_t wi = 0; wi < c.worlds.size(); ++wi) {\n    int r = abort_world_locked(c, *c.worlds[wi]);"),
-    ("broadcast descriptor starts with rank 0 instead of the root", "        l.buf[at++] = f.post[rt].buf;\n        for (int r = 0; r < n; ++r)\n          if (r != rt) l.buf[at++] = f.post[r].buf;",
-     "        for (int r = 0; r < n; ++r) l.buf[at++] = f.post[r].buf;"),
+    ("broadcast descriptor starts with rank 0 instead of the root", "      l.buf[at++] = f.post[rt].buf;\n      for (int r = 0; r < n; ++r)\n        if (r != rt) l.buf[at++] = f.post[r].buf;",
+     "      for (int r = 0; r < n; ++r) l.buf[at++] = f.post[r].buf;"),
     ("copy descriptor has source and destination swapped", "  l.buf[0] = pair[0].buf;\n  l.buf[1] = pair[1].buf;", "  l.buf[0] = pair[1].buf;\n  l.buf[1] = pair[0].buf;"),
     ("live handles are recycled", "    if (e.status.load(std::memory_order_relaxed) == MW_PENDING) continue;  // still live: never recycle\n", ""),
     ("ring slots are never given back", "  slot_release(w, op.l.slot - w.first_slot);\n  op.state = kOpFree;", "  op.state = kOpFree;"),
