@@ -84,7 +84,9 @@ MW_MB_HD inline bool before(uint32_t a, uint32_t b) { return (int32_t)(a - b) < 
 // Which of W workers runs chunk c of a descriptor: chunks are dealt round-robin in the order they were queued
 // (`start` counts the chunks of every earlier ticket), so a window of one-chunk messages and the chunks of a few
 // larger operations both spread evenly over the workers.
-MW_MB_HD inline uint32_t owner(uint32_t start, uint32_t chunk, uint32_t n_workers) { return (start + chunk) % n_workers; }
+MW_MB_HD inline uint32_t owner(uint32_t start, uint32_t chunk, uint32_t n_workers) {
+  return (start % n_workers + chunk % n_workers) % n_workers;  // (no 32-bit wrap inside one descriptor)
+}
 
 // Host side.  Port provides:
 //   void write_desc(uint32_t index, const Desc& d)   store a descriptor into queue slot `index`
