@@ -253,19 +253,20 @@ int mw_pending_ops(void);
 int mw_poll_many(const mw_handle* handles, int n, int* states);
 
 /* Tunables.  key: "chunk_bytes" (power of two, 4096..4194304; 0 = choose per launch), "reduce_lds" (0/1: stage
- * all-reduce tiles through LDS), "mailbox" (0/1, see below) -- these three may be set at any time; "ring_depth" (1..256
+ * all-reduce tiles through LDS), "mailbox" (0/1, see below), "mailbox_idle_us" (10..50000, default 300) -- these four may be set at any time; "ring_depth" (1..256
  * slots per world, default 128), "max_rings", "handle_capacity", "mailbox_workers" (1..1023, default 255) -- only before
  * mw_init.  MW_EINVAL for unknown keys or bad values.
  *
- * "mailbox" = 1 turns on the resident mailbox kernel: a flush whose operations have final buffers (no busy caller
+ * "mailbox" = 1 (the default) turns on the resident mailbox kernel: a flush whose operations have final buffers (no busy caller
  * stream) and move at most 64 MiB together is not launched but written as descriptors into a queue in device memory
  * that a resident kernel serves (one leader that admits descriptors and decides when the kernel ends, and
  * mailbox_workers workgroups that move the data), so a small operation does not pay a kernel launch (Sec. 3.2 / 3.3:
  * a worker busy-waits on its operation, so that latency is what it sees).  Results, completion and polling are
  * the same as for launched operations.  The kernel is started on demand and never waited for; it ends by itself
- * when the host asks (a larger flush wants the whole chip; mw_shutdown), after 300 us without work, and after 100 ms
+ * when the host asks (a larger flush wants the whole chip; mw_shutdown), after mailbox_idle_us without work, and after 100 ms
  * at the latest; operations that arrive just as it ends are served by the next one, which the following mw_flush or
- * mw_poll starts.  Off by default. */
+ * mw_poll starts.  While a kernel is open a device-wide synchronisation by the caller waits for it to end (at most the
+ * idle time); stream-level synchronisation does not.  With 0 every flush is launched. */
 int mw_config_set(const char* key, long value);
 long mw_config_get(const char* key);
 
@@ -283,7 +284,8 @@ const char* mw_build_id(void);
  * kernel kind `kind` (0 copy incl. gather / scatter segments, 1 fan-out: broadcast and all-gather, 2 reduce:
  * all-reduce and reduce): number of launches, total milliseconds
  * and total payload-descriptor bytes (sum of nbytes over operations).  Reading waits for the
- * recorded events (blocks); it is for benchmarks, not for the data path. */
+ * recorded events (blocks); it is for benchmarks, not for the data path.  Operations served by the resident mailbox
+ * kernel are not launches and are not counted: set "mailbox" to 0 to time every operation's kernel. */
 int mw_profile_enable(int on);
 int mw_profile_read(int kind, uint64_t* launches, double* total_ms, uint64_t* op_bytes);
 

@@ -805,6 +805,7 @@ class HipDevice : public Device {
     if (cfg_.mailbox && !cfg.mailbox) mb_.stop();
     cfg_.mailbox = cfg.mailbox;
     cfg_.mailbox_workers = std::min(1023u, std::max(1u, cfg.mailbox_workers));
+    cfg_.mailbox_idle_us = std::min(50000u, std::max(10u, cfg.mailbox_idle_us));  // (takes effect with the next kernel)
   }
 
   int launch(const LaunchOp* ops, const OpDeps* deps, int n, uint8_t* launched) override {
@@ -1018,6 +1019,7 @@ class HipDevice : public Device {
     // The mailbox: queue (process-lifetime, fine-grained), leader's word, closing word, stream.  A GPU that cannot
     // give host-writable device memory simply has no mailbox: every flush is launched.
     cfg_.mailbox_workers = std::min(1023u, std::max(1u, cfg.mailbox_workers));
+    cfg_.mailbox_idle_us = std::min(50000u, std::max(10u, cfg.mailbox_idle_us));
     mb_.reset();
     if (hip_device < kMaxHipDevices) {
       if (!g_mailbox_mem[hip_device]) {
@@ -1474,7 +1476,7 @@ class HipDevice : public Device {
   int launch(uint32_t epoch, uint32_t first) {
     if (chk(hipSetDevice(dev_))) return MW_EHIP;
     hipLaunchKernelGGL(mw_k_mailbox, dim3(cfg_.mailbox_workers + 1), dim3(kCopyWG), 0, mb_stream_, mb_hw_, mb_lw_, mb_closed_dev_, epoch,
-                       first, cfg_.mailbox_workers, kMailboxIdleTicks, kMailboxLifeTicks, slots_, flags_dev_);
+                       first, cfg_.mailbox_workers, (uint64_t)cfg_.mailbox_idle_us * kTicksPerUs, kMailboxLifeTicks, slots_, flags_dev_);
     return chk(hipGetLastError()) ? MW_EHIP : MW_OK;
   }
   bool needs_attention() override { return mb_hw_ && mb_.needs_attention(); }
@@ -1489,8 +1491,9 @@ class HipDevice : public Device {
   // A flush of at most this much traffic goes to the mailbox (the all-reduce iteration of the tensor-parallel
   // workload is 36 MiB); above it the launch overhead no longer matters and the whole chip is wanted.
   static constexpr uint64_t kMailboxMaxTraffic = 64ull << 20;
-  // wall_clock64() ticks at 100 MHz: the resident kernel closes after 300 us without work and lives 100 ms at most
-  static constexpr uint64_t kMailboxIdleTicks = 30000, kMailboxLifeTicks = 10000000;
+  // wall_clock64() ticks at 100 MHz: the resident kernel closes after mailbox_idle_us without work (300 us unless
+  // configured) and lives 100 ms at most
+  static constexpr uint64_t kTicksPerUs = 100, kMailboxLifeTicks = 10000000;
   mb::HostWritten* mb_hw_ = nullptr;         // the queue (fine-grained device memory, host-writable)
   mb::LeaderWritten* mb_lw_ = nullptr;       // the leader's word (device memory)
   uint64_t* mb_closed_ = nullptr;            // what the last leader to close left (host-pinned) ...

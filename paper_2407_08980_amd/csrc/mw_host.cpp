@@ -165,7 +165,7 @@ std::mutex g_wd_mu;  // guards g_wd_thread / g_wd_running
 std::atomic<bool> g_wd_stop{false};
 bool g_wd_running = false;
 long g_cfg_chunk = 0, g_cfg_depth = kDefaultRingDepth, g_cfg_lds = 0, g_cfg_rings = 1024, g_cfg_handles = 1 << 20;
-long g_cfg_mailbox = 1, g_cfg_mailbox_workers = 255;
+long g_cfg_mailbox = 1, g_cfg_mailbox_workers = 255, g_cfg_mailbox_idle_us = 300;
 
 inline mw_handle make_handle(uint32_t slot, uint32_t gen) { return ((uint64_t)gen << 32) | slot; }
 
@@ -654,6 +654,7 @@ int mw_init(int hip_device, int n_workers) {
   c->cfg.reduce_lds = (uint32_t)g_cfg_lds;
   c->cfg.mailbox = (uint32_t)g_cfg_mailbox;
   c->cfg.mailbox_workers = (uint32_t)g_cfg_mailbox_workers;
+  c->cfg.mailbox_idle_us = (uint32_t)g_cfg_mailbox_idle_us;
   c->dev.reset(make_device());
   int rc = c->dev->init(hip_device, c->cfg);
   if (rc != MW_OK) return rc;
@@ -1138,6 +1139,15 @@ int mw_config_set(const char* key, long value) {
     }
     return MW_OK;
   }
+  if (!std::strcmp(key, "mailbox_idle_us")) {
+    if (value < 10 || value > 50000) return MW_EINVAL;
+    g_cfg_mailbox_idle_us = value;
+    if (live) {
+      g_ctx->cfg.mailbox_idle_us = (uint32_t)value;
+      g_ctx->dev->set_config(g_ctx->cfg);
+    }
+    return MW_OK;
+  }
   // geometry: only before mw_init
   if (live) return MW_EINVAL;
   if (!std::strcmp(key, "mailbox_workers")) {
@@ -1170,6 +1180,7 @@ long mw_config_get(const char* key) {
   if (!std::strcmp(key, "reduce_lds")) return g_cfg_lds;
   if (!std::strcmp(key, "mailbox")) return g_cfg_mailbox;
   if (!std::strcmp(key, "mailbox_workers")) return g_cfg_mailbox_workers;
+  if (!std::strcmp(key, "mailbox_idle_us")) return g_cfg_mailbox_idle_us;
   if (!std::strcmp(key, "ring_depth")) return g_cfg_depth;
   if (!std::strcmp(key, "max_rings")) return g_cfg_rings;
   if (!std::strcmp(key, "handle_capacity")) return g_cfg_handles;

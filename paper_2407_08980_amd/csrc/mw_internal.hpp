@@ -108,6 +108,7 @@ struct DeviceConfig {
   uint32_t reduce_lds;    // stage all-reduce tiles through LDS
   uint32_t mailbox;       // serve small flushes through the resident mailbox kernel instead of launching
   uint32_t mailbox_workers;  // workgroups of the resident kernel that move data (1..1023)
+  uint32_t mailbox_idle_us;  // the resident kernel ends after this long without a new descriptor
 };
 
 class Device {

@@ -2,7 +2,10 @@
 // recv, flush, poll the recv until it reports done (arXiv 2407.08980 Sec. 3.2: non-blocking operations whose status
 // the worker polls; Sec. 4.3 measures small messages, where this time is the whole cost).
 //
-//   pingpong.bin [--iters N] [--sizes BYTES,BYTES,...]
+//   pingpong.bin [--iters N] [--sizes BYTES,BYTES,...] [--gap-us T]
+//
+// --gap-us leaves T microseconds between one message's completion and the next post (default 0: back to back); with a
+// gap beyond the resident kernel's idle time every message finds it closed and has to start it.
 //
 // For every size, with small flushes served by the resident mailbox kernel and with every flush launched, it prints
 // one JSON line: medians (and the 10th / 90th percentile of the total) of the three phases in microseconds.
@@ -40,10 +43,13 @@ static double now() { return std::chrono::duration<double>(std::chrono::steady_c
 
 int main(int argc, char** argv) {
   int iters = 2000;
+  double gap_us = 0.0;
   std::vector<size_t> sizes = {4096, 32768, 262144};
   for (int i = 1; i < argc; ++i) {
     if (!std::strcmp(argv[i], "--iters") && i + 1 < argc) {
       iters = std::max(10, std::atoi(argv[++i]));
+    } else if (!std::strcmp(argv[i], "--gap-us") && i + 1 < argc) {
+      gap_us = std::min(1e6, std::max(0.0, std::atof(argv[++i])));
     } else if (!std::strcmp(argv[i], "--sizes") && i + 1 < argc) {
       sizes.clear();
       std::string s = argv[++i];
@@ -59,7 +65,7 @@ int main(int argc, char** argv) {
         at = end + 1;
       }
     } else {
-      std::fprintf(stderr, "usage: %s [--iters N] [--sizes BYTES,BYTES,...]\n", argv[0]);
+      std::fprintf(stderr, "usage: %s [--iters N] [--sizes BYTES,BYTES,...] [--gap-us T]\n", argv[0]);
       return 2;
     }
   }
@@ -103,6 +109,9 @@ int main(int argc, char** argv) {
           return 3;
         }
         if (k >= 0) post[(size_t)k] = t1 - t0, flush[(size_t)k] = t2 - t1, wait[(size_t)k] = t3 - t2, total[(size_t)k] = t3 - t0;
+        if (gap_us > 0.0)
+          while (now() - t3 < gap_us * 1e-6) {
+          }
       }
       HIP_CK(hipMemcpy(back.data(), dst, bytes, hipMemcpyDeviceToHost));
       if (std::memcmp(back.data(), pattern.data(), bytes) != 0) {
@@ -113,9 +122,9 @@ int main(int argc, char** argv) {
         std::sort(v.begin(), v.end());
         return v[(size_t)(q * (double)(v.size() - 1))] * 1e6;
       };
-      std::printf("{\"bytes\": %zu, \"mailbox\": %ld, \"iters\": %d, \"post_us\": %.2f, \"flush_us\": %.2f, \"wait_us\": %.2f, "
+      std::printf("{\"bytes\": %zu, \"mailbox\": %ld, \"iters\": %d, \"gap_us\": %.0f, \"post_us\": %.2f, \"flush_us\": %.2f, \"wait_us\": %.2f, "
                   "\"total_us\": {\"median\": %.2f, \"p10\": %.2f, \"p90\": %.2f}}\n",
-                  bytes, mailbox, iters, pct(post, 0.5), pct(flush, 0.5), pct(wait, 0.5), pct(total, 0.5), pct(total, 0.1), pct(total, 0.9));
+                  bytes, mailbox, iters, gap_us, pct(post, 0.5), pct(flush, 0.5), pct(wait, 0.5), pct(total, 0.5), pct(total, 0.1), pct(total, 0.9));
       std::fflush(stdout);
     }
     MW_CK(mw_shutdown());

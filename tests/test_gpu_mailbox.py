@@ -142,6 +142,37 @@ def test_the_resident_kernel_ends_by_itself_and_the_next_one_takes_over(mailbox,
         assert time.time() - t0 < 2.0
 
 
+def test_the_idle_time_is_configurable(mailbox, torch):
+    """"mailbox_idle_us": with 20 ms the kernel is still open 2 ms after its last message and closes by itself later."""
+    mw = mailbox
+    before = mw.mw_config_get("mailbox_idle_us")
+    assert before == 300
+    with pytest.raises(mw.MwError):
+        mw.mw_config_set("mailbox_idle_us", 5)
+    mw.mw_config_set("mailbox_idle_us", 20000)
+    mw.mw_init(0, 2)
+    try:
+        mw.mw_world_create(0, [0, 1])
+        src = torch.arange(1024, dtype=torch.int32, device="cuda")
+        dst = torch.zeros(1024, dtype=torch.int32, device="cuda")
+        torch.cuda.current_stream().synchronize()
+        hs = [mw.mw_send(0, 0, 1, src.data_ptr(), 1024, mw.MW_F32, mw.STREAM_NONE),
+              mw.mw_recv(0, 0, 1, dst.data_ptr(), 1024, mw.MW_F32, mw.STREAM_NONE)]
+        assert _wait(mw, hs) == [mw.MW_DONE] * 2
+        t_done = time.time()
+        time.sleep(0.002)
+        still_open = mw.mw_debug_mailbox()[1]
+        late = time.time() - t_done > 0.015  # (a stalled host: the check would say nothing)
+        assert still_open == 1 or late
+        while mw.mw_debug_mailbox()[1]:
+            assert time.time() - t_done < 5.0, "the resident kernel did not end when idle"
+        assert time.time() - t_done >= 0.015
+        assert bool(torch.equal(src, dst))
+    finally:
+        mw.mw_shutdown()
+        mw.mw_config_set("mailbox_idle_us", before)
+
+
 def test_more_descriptors_than_one_kernel_serves(mailbox, torch):
     """A resident kernel serves at most half the queue (2048 descriptors); 6000 one-chunk messages in windows of 16
     go through several kernels, with some windows launched the ordinary way while one kernel ends and the next has
