@@ -1021,7 +1021,12 @@ class HipDevice : public Device {
     cfg_.mailbox_workers = std::min(1023u, std::max(1u, cfg.mailbox_workers));
     cfg_.mailbox_idle_us = std::min(50000u, std::max(10u, cfg.mailbox_idle_us));
     mb_.reset();
-    if (hip_device < kMaxHipDevices) {
+    int large_bar = 0;  // the host writes the queue with plain stores: the whole device memory must be in its address space
+    if (hipDeviceGetAttribute(&large_bar, hipDeviceAttributeIsLargeBar, hip_device) != hipSuccess) {
+      (void)hipGetLastError();
+      large_bar = 0;
+    }
+    if (hip_device < kMaxHipDevices && large_bar) {
       if (!g_mailbox_mem[hip_device]) {
         void* p = nullptr;
         if (hipExtMallocWithFlags(&p, sizeof(mb::HostWritten), hipDeviceMallocFinegrained) == hipSuccess) g_mailbox_mem[hip_device] = static_cast<mb::HostWritten*>(p);
@@ -1031,6 +1036,14 @@ class HipDevice : public Device {
     }
     if (mb_hw_) {
       if (chk(hipMemset(mb_hw_, 0, 128))) return MW_EHIP;  // doorbell and stop word
+      // Do the host's stores arrive?  Write a pattern the way descriptors are written, read it back with a copy.
+      uint32_t probe[4] = {0x6d61696cu, 0x626f7821u, (uint32_t)hip_device, 0x00c0ffeeu}, back[4] = {};
+      _mm_stream_si128(reinterpret_cast<__m128i*>(&mb_hw_->pad[2]), _mm_loadu_si128(reinterpret_cast<const __m128i*>(probe)));
+      _mm_sfence();
+      if (chk(hipMemcpy(back, &mb_hw_->pad[2], sizeof(back), hipMemcpyDeviceToHost))) return MW_EHIP;
+      if (std::memcmp(probe, back, sizeof(probe)) != 0) mb_hw_ = nullptr;  // no mailbox on this machine: every flush is launched
+    }
+    if (mb_hw_) {
       if (chk(hipMalloc(reinterpret_cast<void**>(&mb_lw_), sizeof(mb::LeaderWritten))) || chk(hipMemset(mb_lw_, 0, sizeof(mb::LeaderWritten)))) return MW_EHIP;
       if (chk(hipHostMalloc(reinterpret_cast<void**>(&mb_closed_), 64, hipHostMallocMapped | hipHostMallocCoherent))) return MW_EHIP;
       *mb_closed_ = 0;
