@@ -284,8 +284,8 @@ const char* mw_build_id(void);
  * kernel kind `kind` (0 copy incl. gather / scatter segments, 1 fan-out: broadcast and all-gather, 2 reduce:
  * all-reduce and reduce): number of launches, total milliseconds
  * and total payload-descriptor bytes (sum of nbytes over operations).  Reading waits for the
- * recorded events (blocks); it is for benchmarks, not for the data path.  Operations served by the resident mailbox
- * kernel are not launches and are not counted: set "mailbox" to 0 to time every operation's kernel. */
+ * recorded events (blocks); it is for benchmarks, not for the data path.  While timing is enabled every flush is
+ * launched (work done by the resident mailbox kernel cannot be bracketed by events). */
 int mw_profile_enable(int on);
 int mw_profile_read(int kind, uint64_t* launches, double* total_ms, uint64_t* op_bytes);
 

@@ -1246,7 +1246,7 @@ class HipDevice : public Device {
         bytes[k] += ops[i].nbytes * ops[i].nbuf * (k == kReduce ? 2 : 1);
         n_mine += 1;
       }
-      if (cfg_.mailbox && mb_hw_ && n_mine) {
+      if (cfg_.mailbox && mb_hw_ && n_mine && !profiling_) {  // (kernel timing brackets launches: while it is on, everything is launched)
         // A small flush goes to the resident kernel: no launch.  A larger one wants the whole chip: the resident
         // kernel is asked to close (it does within a microsecond or two; nobody waits for it).
         const uint64_t traffic = bytes[kCopy] + bytes[kBcast] + bytes[kReduce];
