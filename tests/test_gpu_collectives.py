@@ -24,14 +24,19 @@ def torch():
     return torch
 
 
-@pytest.fixture
-def mw(torch):
+@pytest.fixture(params=[1, 0], ids=["mailbox", "launched"])
+def mw(torch, request):
+    """Every test of this module runs twice: with small flushes served by the resident mailbox kernel (the library's
+    default) and with every flush launched."""
     from paper_2407_08980_amd import binding
 
     binding.lib()
+    before = binding.mw_config_get("mailbox")
+    binding.mw_config_set("mailbox", request.param)
     binding.mw_init(0, 16)
     yield binding
     binding.mw_shutdown()
+    binding.mw_config_set("mailbox", before)
 
 
 def wait(mw, handles, timeout=60.0):

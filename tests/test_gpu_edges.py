@@ -23,14 +23,19 @@ def torch():
     return torch
 
 
-@pytest.fixture
-def mw(torch):
+@pytest.fixture(params=[1, 0], ids=["mailbox", "launched"])
+def mw(torch, request):
+    """Every test of this module runs twice: with small flushes served by the resident mailbox kernel (the library's
+    default) and with every flush launched."""
     from paper_2407_08980_amd import binding
 
     binding.lib()
+    before = binding.mw_config_get("mailbox")
+    binding.mw_config_set("mailbox", request.param)
     binding.mw_init(0, 16)
     yield binding
     binding.mw_shutdown()
+    binding.mw_config_set("mailbox", before)
 
 
 def wait(mw, handles, timeout=60.0):
@@ -48,6 +53,15 @@ def dev_bytes(torch, arr, offset=0, pad=64):
     view = base[offset:offset + arr.size]
     view.copy_(torch.from_numpy(arr))
     return base, view
+
+
+def served_as_configured(mw):
+    """With the mailbox on, flushes of this test went through the queue; with it off, none did."""
+    epoch, _, tail = mw.mw_debug_mailbox()
+    if mw.mw_config_get("mailbox"):
+        assert epoch >= 1 and tail >= 1
+    else:
+        assert (epoch, tail) == (0, 0)
 
 
 def rand_bytes(n, seed):
@@ -68,6 +82,7 @@ def test_copy_any_alignment_and_ragged_sizes(torch, mw, soff, doff):
         assert np.array_equal(got[doff:doff + nbytes], oracle.copy_result(src))
         assert np.all(got[:doff] == 0x5A) and np.all(got[doff + nbytes:] == 0x5A)  # nothing outside is touched
         assert np.array_equal(sview.cpu().numpy(), src)
+    served_as_configured(mw)
 
 
 @pytest.mark.parametrize("n", [2, 3, 5, 8])
@@ -83,6 +98,7 @@ def test_broadcast_every_root_up_to_eight_ranks(torch, mw, n):
         want = oracle.broadcast_result(host, root)
         for r in range(n):
             assert np.array_equal(dev[r][1].cpu().numpy(), want[r]), (root, r)
+    served_as_configured(mw)
 
 
 @pytest.mark.parametrize("lds", [0, 1])
@@ -109,6 +125,7 @@ def test_allreduce_world_sizes_alignment_and_tails(torch, mw, n, dtype, lds):
                 assert np.array_equal(got, ordered), (n, dtype, count, r)  # fixed order: bit-exact, same on all ranks
                 base = dev[r][0].cpu().numpy()
                 assert np.all(base[: off_elems * isz] == 0x5A) and np.all(base[off_elems * isz + count * isz:] == 0x5A)
+        served_as_configured(mw)
     finally:
         mw.mw_config_set("reduce_lds", 0)
 
