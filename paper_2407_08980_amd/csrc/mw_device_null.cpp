@@ -3,6 +3,7 @@
 // that the host state machine (matching, handles, ring slots, abort, deferred ring
 // release) can be exercised on a machine without a GPU.  "Launches" are recorded;
 // the test decides when the recorded operations complete.
+#include <atomic>
 #include <cstring>
 #include <deque>
 #include <mutex>
@@ -28,6 +29,8 @@ struct NullState {
   std::vector<int> launch_streams;    // distinct streams waited on per launch
   int marks = 0;
   bool fail_next_launch = false;
+  std::atomic<bool> attention{false};  // "queued work wants a kernel started"
+  std::atomic<int> attends{0};         // how often the host runtime looked after it
   std::mutex mu;  // the test hooks may run on another thread than the library calls
 };
 NullState* g_null = nullptr;
@@ -74,8 +77,13 @@ class NullDevice : public Device {
     for (int i = 0; i < n; ++i) st_.log.push_back(Recorded{ops[i], id});  // complete by stream order: never pending
     return MW_OK;
   }
-  bool needs_attention() override { return false; }
-  int attend() override { return MW_OK; }
+  // The double has no resident kernel; a test can make it say that queued work wants a kernel started (as the product's
+  // backend does when its kernel closed with descriptors left) and count how often the host runtime then looks after it.
+  bool needs_attention() override { return st_.attention.load(std::memory_order_acquire); }
+  int attend() override {
+    if (st_.attention.exchange(false)) st_.attends.fetch_add(1);
+    return MW_OK;
+  }
   void mailbox_state(uint32_t* epoch, uint32_t* open, uint32_t* tail) override { *epoch = *open = *tail = 0; }
   int mark_world(uint32_t ring_index, const RingHeader& h) override {
     std::lock_guard<std::mutex> g(st_.mu);
@@ -164,6 +172,14 @@ int mwt_complete(int n, int from_back) {
   }
   return done;
 }
+
+// Make needs_attention() true until the host runtime calls attend(); mwt_attends() counts those calls.
+int mwt_want_attention(void) {
+  if (!g_null) return -1;
+  g_null->attention.store(true, std::memory_order_release);
+  return 0;
+}
+int mwt_attends(void) { return g_null ? g_null->attends.load() : -1; }
 
 int mwt_fail_next_launch(void) {
   if (!g_null) return -1;

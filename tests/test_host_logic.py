@@ -321,6 +321,27 @@ def test_launch_failure_is_reported_and_nothing_is_lost(ctx):
     assert mw.mw_poll(h) == mw.MW_DONE
 
 
+def test_polls_and_flushes_look_after_work_left_without_a_kernel(ctx):
+    """When the backend says that queued work has no kernel to serve it (its resident kernel closed as the work came
+    in), the next poll of a pending operation -- also the lock-free kind -- and the next flush must have it looked after."""
+    mw.mw_world_create(0, [0, 1])
+    mw.mw_send(0, 0, 1, 0x10, 1, mw.MW_F32)
+    h = mw.mw_recv(0, 0, 1, 0x20, 1, mw.MW_F32)
+    mw.mw_flush()  # in flight, not complete
+    assert mw.mw_poll(h) == mw.MW_PENDING and ctx.mwt_attends() == 0
+    ctx.mwt_want_attention()
+    assert mw.mw_poll(h) == mw.MW_PENDING and ctx.mwt_attends() == 1
+    assert mw.mw_poll(h) == mw.MW_PENDING and ctx.mwt_attends() == 1  # once is enough
+    ctx.mwt_want_attention()
+    ps = mw.PollSet([h])
+    assert ps.poll() == 1 and ctx.mwt_attends() == 2  # mw_poll_many too
+    ctx.mwt_want_attention()
+    mw.mw_flush()
+    assert ctx.mwt_attends() == 3
+    ctx.mwt_complete(1, 0)
+    assert mw.mw_poll(h) == mw.MW_DONE
+
+
 def test_streams_are_deduplicated_and_none_is_skipped(ctx):
     mw.mw_world_create(0, [0, 1])
     mw.mw_world_create(1, [2, 3])

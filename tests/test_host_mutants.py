@@ -41,6 +41,11 @@ MUTANTS = [
     ("a poll without the lock never looks at the completion word", "(fs != kNone && c.dev->flag(fs) != fg && !c.dev->needs_attention())", "(fs != kNone && !c.dev->needs_attention())"),
     ("a poll without the lock takes a launched operation for a complete one", "  if (st != MW_PENDING) {\n    *state = st;\n    return true;\n  }\n  if (op == kNone",
      "  if (st != MW_PENDING || fs != kNone) {\n    *state = fs != kNone ? MW_DONE : st;\n    return true;\n  }\n  if (op == kNone"),
+    ("a poll without the lock does not notice work left without a kernel", "(fs != kNone && c.dev->flag(fs) != fg && !c.dev->needs_attention())",
+     "(fs != kNone && c.dev->flag(fs) != fg)"),
+    ("a poll under the lock does not start a kernel for work left without one",
+     "  if (c.dev->needs_attention()) {  // it may sit in the resident kernel's queue with no kernel open: start one\n    int rc = c.dev->attend();\n    if (rc != MW_OK) return rc;\n  }\n",
+     ""),
     ("the allocation-free variant pairs a side with a side of its own kind", "posts[j].kind == 1 - p.kind", "posts[j].kind == p.kind"),
     ("the allocation-free variant lets a rank's later collective overtake its earlier one",
      "posts[j].world_id == p.world_id && side[posts[j].a] < 0)\n          side[posts[j].a] = j;",
