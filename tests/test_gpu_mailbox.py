@@ -67,6 +67,18 @@ def test_config3_through_the_mailbox(mailbox, host_pools, dtype):
     assert tail == 12 * 8
 
 
+def test_config3_full_length_through_the_mailbox(mailbox, host_pools):
+    """The tensor-parallel workload at its full length: 500 iterations of 8 all-reduces, every one a descriptor in the
+    queue (4000, i.e. more than one resident kernel serves), data checked on 12 iterations."""
+    checked = [0, 1, 2, 3, 4, 5, 250, 251, 496, 497, 498, 499]
+    t = workloads.config3(iters=500, check_iters=checked)
+    orun, grun, (epoch, _, tail) = _both(t, host_pools)
+    rep = compare_runs(t, orun, grun)
+    assert rep["toleranced"] == len(checked) * 32 and rep["worst_allreduce_ratio"] <= 3 * 2.0 ** -24
+    assert all(v == "done" for v in grun.status.values()) and len(grun.status) == 500 * 32
+    assert epoch >= 2 and 3000 <= tail <= 500 * 8  # (a few flushes are launched while one kernel hands over to the next)
+
+
 def test_mixed_operations_aborts_and_sizes_through_the_mailbox(mailbox, host_pools):
     """All eight operations with worker aborts (windows small enough for the queue), then the mixed scale-out recipe
     at small sizes, then the fan-in with a fault: small flushes go through the queue, larger ones are launched while
