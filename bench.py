@@ -1284,6 +1284,8 @@ def main():
     out["config"]["mailbox"] = args.mailbox
     if args.workload == "config1":
         out["single_message_post_to_done_from_c_us"] = pingpong_from_c(8 * 1024 * 4)
+    if args.workload == "config3":
+        out["us_per_iteration_from_c"] = tensor_parallel_loop_from_c()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_of(args)
     print(json.dumps(out))
@@ -1301,6 +1303,25 @@ def pingpong_from_c(nbytes):
     if p.returncode != 0:
         raise RuntimeError("pingpong.bin failed: " + p.stderr[-500:])
     return [json.loads(line) for line in p.stdout.splitlines() if line.startswith("{")]
+
+
+def tensor_parallel_loop_from_c():
+    """The same iteration loop driven by the package's C program (no interpreter between the calls):
+    {"mailbox": {"1": us, ..., "4": us}, "every_flush_launched": {...}} by iterations in flight."""
+    import subprocess
+    from paper_2407_08980_amd import build
+
+    if not os.path.exists(build.PINGPONG):
+        return None
+    p = subprocess.run([build.PINGPONG, "--tp", "--iters", "2000"], capture_output=True, text=True, timeout=180)
+    if p.returncode != 0:
+        raise RuntimeError("pingpong.bin --tp failed: " + p.stderr[-500:])
+    out = {"mailbox": {}, "every_flush_launched": {}}
+    for line in p.stdout.splitlines():
+        if line.startswith("{"):
+            r = json.loads(line)
+            out["mailbox" if r["mailbox"] else "every_flush_launched"][str(r["iterations_in_flight"])] = r["us_per_iteration"]
+    return out
 
 
 def cpu_baseline_config4(steps, abort_step):

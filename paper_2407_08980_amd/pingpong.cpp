@@ -3,6 +3,7 @@
 // the worker polls; Sec. 4.3 measures small messages, where this time is the whole cost).
 //
 //   pingpong.bin [--iters N] [--sizes BYTES,BYTES,...] [--gap-us T]
+//   pingpong.bin --tp [--iters N]
 //
 // --gap-us leaves T microseconds between one message's completion and the next post (default 0: back to back); with a
 // gap beyond the resident kernel's idle time every message finds it closed and has to start it.
@@ -10,6 +11,10 @@
 // For every size, with small flushes served by the resident mailbox kernel and with every flush launched, it prints
 // one JSON line: medians (and the 10th / 90th percentile of the total) of the three phases in microseconds.
 // The payload is checked once per size.
+//
+// --tp runs the tensor-parallel partial-sum loop instead (Sec. 3.1's tensor-parallel stages; 4 worlds x 4 ranks, per
+// iteration every world all-reduces fp32 [16,4096] and [16,14336], inputs U(-1,1)): 1 to 4 iterations in flight, both
+// forms, one JSON line each with the microseconds per iteration.  Results are not checked here (the parity tests do).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -41,12 +46,88 @@ static double now() { return std::chrono::duration<double>(std::chrono::steady_c
     }                                                                   \
   } while (0)
 
+// The tensor-parallel loop: `depth` iterations in flight, each on input buffers of its own (4 sets).
+static int tensor_parallel_loop(int iters) {
+  const int n_worlds = 4, n_ranks = 4, n_sets = 4;
+  const size_t counts[2] = {16 * 4096, 16 * 14336};
+  std::vector<float> host(counts[1]);
+  unsigned long long x = 88172645463325252ull;  // xorshift64: inputs in (-1, 1)
+  std::vector<std::vector<mw_post_desc>> posts((size_t)n_sets);
+  std::vector<void*> bufs;
+  HIP_CK(hipSetDevice(0));
+  for (int k = 0; k < n_sets; ++k)
+    for (int j = 0; j < 2; ++j)
+      for (int w = 0; w < n_worlds; ++w)
+        for (int r = 0; r < n_ranks; ++r) {
+          for (size_t i = 0; i < counts[j]; ++i) {
+            x ^= x << 13, x ^= x >> 7, x ^= x << 17;
+            host[i] = (float)((double)(x >> 11) / 4503599627370496.0 - 1.0);
+          }
+          void* p = nullptr;
+          HIP_CK(hipMalloc(&p, counts[j] * 4));
+          HIP_CK(hipMemcpy(p, host.data(), counts[j] * 4, hipMemcpyHostToDevice));
+          bufs.push_back(p);
+          mw_post_desc d{};
+          d.kind = MW_POST_ALLREDUCE_SUM, d.world_id = w, d.a = r, d.buf = p, d.count = counts[j], d.dtype = MW_F32, d.hip_stream = MW_STREAM_NONE;
+          posts[(size_t)k].push_back(d);
+        }
+  HIP_CK(hipDeviceSynchronize());
+  const int n_posts = (int)posts[0].size();
+  for (long mailbox = 1; mailbox >= 0; --mailbox) {
+    MW_CK(mw_config_set("mailbox", mailbox));
+    MW_CK(mw_init(0, n_worlds * n_ranks));
+    for (int w = 0; w < n_worlds; ++w) {
+      int ids[4];
+      for (int r = 0; r < n_ranks; ++r) ids[r] = w * n_ranks + r;
+      MW_CK(mw_world_create(w, ids, n_ranks));
+    }
+    std::vector<std::vector<mw_handle>> h((size_t)n_sets, std::vector<mw_handle>((size_t)n_posts));
+    std::vector<int> res((size_t)n_posts), st((size_t)n_posts);
+    for (int depth = 1; depth <= n_sets; ++depth) {
+      double us = 0.0;
+      for (int pass = 0; pass < 2; ++pass) {  // the first pass is the warm-up
+        const int n = pass == 0 ? 200 : iters;
+        const double t0 = now();
+        for (int it = 0; it < n; ++it) {
+          const size_t k = (size_t)(it % n_sets);
+          if (it >= depth) {  // the iteration that used this depth's slot must be done (it is the one whose buffers come up next)
+            const size_t o = (size_t)((it - depth) % n_sets);
+            int pending;
+            while ((pending = mw_poll_many(h[o].data(), n_posts, st.data())) > 0) {
+              if (now() - t0 > 30.0) {
+                std::fprintf(stderr, "the loop did not make progress\n");
+                return 3;
+              }
+            }
+            MW_CK(pending);
+          }
+          MW_CK(mw_post_many(posts[k].data(), n_posts, h[k].data(), res.data()));
+          MW_CK(mw_flush());
+        }
+        for (size_t o = 0; o < (size_t)n_sets; ++o)
+          while (mw_poll_many(h[o].data(), n_posts, st.data()) > 0) {
+            if (now() - t0 > 30.0) return 3;
+          }
+        us = (now() - t0) / n * 1e6;
+      }
+      std::printf("{\"workload\": \"tp\", \"mailbox\": %ld, \"iterations_in_flight\": %d, \"iters\": %d, \"us_per_iteration\": %.2f}\n", mailbox, depth, iters, us);
+      std::fflush(stdout);
+    }
+    MW_CK(mw_shutdown());
+  }
+  for (void* p : bufs) (void)hipFree(p);
+  return 0;
+}
+
 int main(int argc, char** argv) {
   int iters = 2000;
+  bool tp = false;
   double gap_us = 0.0;
   std::vector<size_t> sizes = {4096, 32768, 262144};
   for (int i = 1; i < argc; ++i) {
-    if (!std::strcmp(argv[i], "--iters") && i + 1 < argc) {
+    if (!std::strcmp(argv[i], "--tp")) {
+      tp = true;
+    } else if (!std::strcmp(argv[i], "--iters") && i + 1 < argc) {
       iters = std::max(10, std::atoi(argv[++i]));
     } else if (!std::strcmp(argv[i], "--gap-us") && i + 1 < argc) {
       gap_us = std::min(1e6, std::max(0.0, std::atof(argv[++i])));
@@ -65,10 +146,11 @@ int main(int argc, char** argv) {
         at = end + 1;
       }
     } else {
-      std::fprintf(stderr, "usage: %s [--iters N] [--sizes BYTES,BYTES,...] [--gap-us T]\n", argv[0]);
+      std::fprintf(stderr, "usage: %s [--iters N] [--sizes BYTES,BYTES,...] [--gap-us T] | --tp [--iters N]\n", argv[0]);
       return 2;
     }
   }
+  if (tp) return tensor_parallel_loop(iters);
   size_t max_bytes = 0;
   for (size_t b : sizes) max_bytes = std::max(max_bytes, b);
   void *src = nullptr, *dst = nullptr;
