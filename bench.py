@@ -1284,6 +1284,7 @@ def main():
     out["config"]["mailbox"] = args.mailbox
     if args.workload == "config1":
         out["single_message_post_to_done_from_c_us"] = pingpong_from_c(8 * 1024 * 4)
+        out["us_per_message_from_c"] = window_loop_from_c()
     if args.workload == "config3":
         out["us_per_iteration_from_c"] = tensor_parallel_loop_from_c()
     if not args.no_cpu_baseline:
@@ -1303,6 +1304,25 @@ def pingpong_from_c(nbytes):
     if p.returncode != 0:
         raise RuntimeError("pingpong.bin failed: " + p.stderr[-500:])
     return [json.loads(line) for line in p.stdout.splitlines() if line.startswith("{")]
+
+
+def window_loop_from_c():
+    """Windows of 16 messages of 32 KiB driven by the package's C program:
+    {"mailbox": {"1": us per message, "2": ...}, "every_flush_launched": {...}} by windows in flight."""
+    import subprocess
+    from paper_2407_08980_amd import build
+
+    if not os.path.exists(build.PINGPONG):
+        return None
+    p = subprocess.run([build.PINGPONG, "--windows", "--iters", "2000"], capture_output=True, text=True, timeout=180)
+    if p.returncode != 0:
+        raise RuntimeError("pingpong.bin --windows failed: " + p.stderr[-500:])
+    out = {"mailbox": {}, "every_flush_launched": {}}
+    for line in p.stdout.splitlines():
+        if line.startswith("{"):
+            r = json.loads(line)
+            out["mailbox" if r["mailbox"] else "every_flush_launched"][str(r["windows_in_flight"])] = r["us_per_message"]
+    return out
 
 
 def tensor_parallel_loop_from_c():

@@ -4,6 +4,7 @@
 //
 //   pingpong.bin [--iters N] [--sizes BYTES,BYTES,...] [--gap-us T]
 //   pingpong.bin --tp [--iters N]
+//   pingpong.bin --windows [--iters N]
 //
 // --gap-us leaves T microseconds between one message's completion and the next post (default 0: back to back); with a
 // gap beyond the resident kernel's idle time every message finds it closed and has to start it.
@@ -119,14 +120,92 @@ static int tensor_parallel_loop(int iters) {
   return 0;
 }
 
+// Windows of 16 messages of 32 KiB, alternating between two worlds that share worker 0.
+static int window_loop(int iters) {
+  const int window = 16, n_sets = 2;
+  const size_t bytes = 32768;
+  std::vector<unsigned char> pattern(bytes), back(bytes);
+  for (size_t i = 0; i < bytes; ++i) pattern[i] = (unsigned char)(i * 29u + (i >> 7) * 13u + 3u);
+  HIP_CK(hipSetDevice(0));
+  std::vector<std::vector<mw_post_desc>> posts((size_t)n_sets);
+  std::vector<void*> bufs, dsts;
+  for (int k = 0; k < n_sets; ++k)
+    for (int m = 0; m < window; ++m) {
+      void *src = nullptr, *dst = nullptr;
+      HIP_CK(hipMalloc(&src, bytes));
+      HIP_CK(hipMalloc(&dst, bytes));
+      HIP_CK(hipMemcpy(src, pattern.data(), bytes, hipMemcpyHostToDevice));
+      HIP_CK(hipMemset(dst, 0, bytes));
+      bufs.push_back(src), bufs.push_back(dst), dsts.push_back(dst);
+      mw_post_desc d{};
+      d.world_id = m % 2, d.a = 1, d.b = 0, d.count = bytes / 4, d.dtype = MW_F32, d.hip_stream = MW_STREAM_NONE;
+      d.kind = MW_POST_SEND, d.buf = src;
+      posts[(size_t)k].push_back(d);
+      d.kind = MW_POST_RECV, d.buf = dst;
+      posts[(size_t)k].push_back(d);
+    }
+  HIP_CK(hipDeviceSynchronize());
+  const int n_posts = 2 * window;
+  for (long mailbox = 1; mailbox >= 0; --mailbox) {
+    MW_CK(mw_config_set("mailbox", mailbox));
+    MW_CK(mw_init(0, 3));
+    const int a[2] = {0, 1}, b[2] = {0, 2};
+    MW_CK(mw_world_create(0, a, 2));
+    MW_CK(mw_world_create(1, b, 2));
+    std::vector<std::vector<mw_handle>> h((size_t)n_sets, std::vector<mw_handle>((size_t)n_posts));
+    std::vector<int> res((size_t)n_posts), st((size_t)n_posts);
+    for (int depth = 1; depth <= n_sets; ++depth) {
+      double us = 0.0;
+      for (int pass = 0; pass < 2; ++pass) {  // the first pass is the warm-up
+        const int n = pass == 0 ? 200 : iters;
+        const double t0 = now();
+        for (int it = 0; it < n; ++it) {
+          const size_t k = (size_t)(it % n_sets);
+          if (it >= depth) {
+            const size_t o = (size_t)((it - depth) % n_sets);
+            while (mw_poll_many(h[o].data(), n_posts, st.data()) > 0) {
+              if (now() - t0 > 30.0) {
+                std::fprintf(stderr, "the loop did not make progress\n");
+                return 3;
+              }
+            }
+          }
+          MW_CK(mw_post_many(posts[k].data(), n_posts, h[k].data(), res.data()));
+          MW_CK(mw_flush());
+        }
+        for (size_t o = 0; o < (size_t)n_sets; ++o)
+          while (mw_poll_many(h[o].data(), n_posts, st.data()) > 0) {
+            if (now() - t0 > 30.0) return 3;
+          }
+        us = (now() - t0) / n / window * 1e6;
+      }
+      std::printf("{\"workload\": \"windows\", \"mailbox\": %ld, \"windows_in_flight\": %d, \"window\": %d, \"iters\": %d, \"us_per_message\": %.3f}\n",
+                  mailbox, depth, window, iters, us);
+      std::fflush(stdout);
+    }
+    MW_CK(mw_shutdown());
+  }
+  for (void* d : dsts) {
+    HIP_CK(hipMemcpy(back.data(), d, bytes, hipMemcpyDeviceToHost));
+    if (std::memcmp(back.data(), pattern.data(), bytes) != 0) {
+      std::fprintf(stderr, "payload differs\n");
+      return 4;
+    }
+  }
+  for (void* p : bufs) (void)hipFree(p);
+  return 0;
+}
+
 int main(int argc, char** argv) {
   int iters = 2000;
-  bool tp = false;
+  bool tp = false, windows = false;
   double gap_us = 0.0;
   std::vector<size_t> sizes = {4096, 32768, 262144};
   for (int i = 1; i < argc; ++i) {
     if (!std::strcmp(argv[i], "--tp")) {
       tp = true;
+    } else if (!std::strcmp(argv[i], "--windows")) {
+      windows = true;
     } else if (!std::strcmp(argv[i], "--iters") && i + 1 < argc) {
       iters = std::max(10, std::atoi(argv[++i]));
     } else if (!std::strcmp(argv[i], "--gap-us") && i + 1 < argc) {
@@ -146,11 +225,12 @@ int main(int argc, char** argv) {
         at = end + 1;
       }
     } else {
-      std::fprintf(stderr, "usage: %s [--iters N] [--sizes BYTES,BYTES,...] [--gap-us T] | --tp [--iters N]\n", argv[0]);
+      std::fprintf(stderr, "usage: %s [--iters N] [--sizes BYTES,BYTES,...] [--gap-us T] | --tp [--iters N] | --windows [--iters N]\n", argv[0]);
       return 2;
     }
   }
   if (tp) return tensor_parallel_loop(iters);
+  if (windows) return window_loop(iters);
   size_t max_bytes = 0;
   for (size_t b : sizes) max_bytes = std::max(max_bytes, b);
   void *src = nullptr, *dst = nullptr;

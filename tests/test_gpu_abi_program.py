@@ -58,3 +58,16 @@ def test_the_latency_programs_tensor_parallel_loop_runs_in_both_forms():
     assert [(r["mailbox"], r["iterations_in_flight"]) for r in rows] == [(m, d) for m in (1, 0) for d in (1, 2, 3, 4)]
     print({(r["mailbox"], r["iterations_in_flight"]): r["us_per_iteration"] for r in rows})
     assert all(0 < r["us_per_iteration"] < 1000 for r in rows)
+
+
+@pytest.mark.gpu
+def test_the_latency_programs_window_loop_moves_the_right_bytes():
+    import json
+
+    from paper_2407_08980_amd import build
+
+    p = subprocess.run([build.PINGPONG, "--windows", "--iters", "300"], capture_output=True, text=True, timeout=180)
+    assert p.returncode == 0, p.stdout[-1000:] + p.stderr[-1000:]  # (it checks the payload itself)
+    rows = [json.loads(line) for line in p.stdout.splitlines() if line.startswith("{")]
+    assert [(r["mailbox"], r["windows_in_flight"]) for r in rows] == [(m, d) for m in (1, 0) for d in (1, 2)]
+    print({(r["mailbox"], r["windows_in_flight"]): r["us_per_message"] for r in rows})
