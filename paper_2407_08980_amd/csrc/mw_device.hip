@@ -1058,6 +1058,7 @@ class HipDevice : public Device {
     op_chunks_.reserve(512);
     chunk_bytes_.reserve(512);
     targets_.reserve(512);
+    first_chunk_.reserve(512);
     group_of_.reserve(4096);
     static_launched_.reserve(kStaticOps);
     if (chk(hipDeviceSynchronize())) return MW_EHIP;
@@ -1319,21 +1320,28 @@ class HipDevice : public Device {
       chunks += chunks_[(size_t)i];
     }
     if (chunks == 0 || chunks > 0x7FFFFFFFull) return fail_inval();
-    if (via_mailbox_) return mailbox_entries(kind);
     // Per operation: its chunk count, and the arrival count at which it is complete -- the slot's running total
     // (counts_) plus its chunks.  An operation of one chunk does not touch the counter.
     op_chunks_.resize((size_t)n);
     targets_.resize((size_t)n);
+    first_chunk_.resize((size_t)n);
     for (int i = 0; i < n;) {
       int j = i;
       uint32_t sum = 0;
-      while (j < n && ents_[(size_t)j].group == ents_[(size_t)i].group) sum += chunks_[(size_t)j++];
+      while (j < n && ents_[(size_t)j].group == ents_[(size_t)i].group) {
+        first_chunk_[(size_t)j] = sum;  // chunks of the same operation in earlier entries
+        sum += chunks_[(size_t)j++];
+      }
       const uint32_t target = counts_[ents_[(size_t)i].slot] + (sum > 1 ? sum : 0);
       for (int k = i; k < j; ++k) {
         op_chunks_[(size_t)k] = sum;
         targets_[(size_t)k] = target;
       }
       i = j;
+    }
+    if (via_mailbox_) {  // no launch: the entries become descriptors in the resident kernel's queue
+      if (int rc = mailbox_entries(kind)) return rc;
+      return entries_are_on_their_way();
     }
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (profiling_) {
@@ -1358,10 +1366,15 @@ class HipDevice : public Device {
       if (chk(hipEventRecord(e1, data_[kind]))) return MW_EHIP;
       prof_.push_back(ProfRec{kind, e0, e1, total_bytes});
     }
-    for (int i = 0; i < n; ++i) {
-      const Ent& e = ents_[(size_t)i];
-      counts_[e.slot] = targets_[(size_t)i];  // the launch is enqueued: its chunks will be counted in
-      launched_[e.group] = 1;                 // group = index of the operation in this launch call
+    return entries_are_on_their_way();
+  }
+
+  // The gathered entries are enqueued (launched, or queued for the resident kernel): their chunks will be counted in.
+  int entries_are_on_their_way() {
+    for (size_t i = 0; i < ents_.size(); ++i) {
+      const Ent& e = ents_[i];
+      counts_[e.slot] = targets_[i];
+      launched_[e.group] = 1;  // group = index of the operation in this launch call
     }
     ents_.clear();
     return MW_OK;
@@ -1424,48 +1437,37 @@ class HipDevice : public Device {
     }
   }
 
-  // The gathered entries (ents_, with chunks_ / chunk_bytes_ filled in) as descriptors for the resident kernel.
+  // The gathered entries (ents_, with chunks_ / chunk_bytes_ / op_chunks_ / targets_ / first_chunk_ filled in) as
+  // descriptors for the resident kernel.  They stay queued whether or not a kernel could be started for them now
+  // (the next flush or poll tries again), so the caller books them as on their way either way.
   int mailbox_entries(uint32_t kind) {
-    const int n = (int)ents_.size();
-    mb_descs_.resize((size_t)n);
-    for (int i = 0; i < n;) {
-      int j = i;
-      uint32_t sum = 0;
-      while (j < n && ents_[(size_t)j].group == ents_[(size_t)i].group) sum += chunks_[(size_t)j++];
-      const uint32_t target = counts_[ents_[(size_t)i].slot] + (sum > 1 ? sum : 0);
-      uint32_t before = 0;
-      for (int k = i; k < j; ++k) {
-        const Ent& e = ents_[(size_t)k];
-        mb::Desc& d = mb_descs_[(size_t)k];
-        std::memset(&d, 0, sizeof(d));
-        for (int b = 0; b < kMaxBufs; ++b) d.buf[b] = e.buf[b];
-        d.nbytes = e.nbytes;
-        d.slot = e.slot;
-        d.gen = e.gen;
-        d.nbuf = e.nbuf;
-        d.chunk_bytes = chunk_bytes_[(size_t)k];
-        d.world_id = e.world_id;
-        d.world_epoch = e.world_epoch;
-        d.op_chunks = sum;
-        d.flags = e.flags;
-        d.target = target;
-        d.kind = kind == kCopy ? mb::kKindCopy : kind == kBcast ? mb::kKindBcast : mb::kKindReduce;
-        d.first_chunk = before;
-        d.n_chunks = chunks_[(size_t)k];
-        before += chunks_[(size_t)k];
-      }
-      i = j;
+    const size_t n = ents_.size();
+    mb_descs_.resize(n);
+    for (size_t k = 0; k < n; ++k) {
+      const Ent& e = ents_[k];
+      mb::Desc& d = mb_descs_[k];
+      std::memset(&d, 0, sizeof(d));
+      for (int b = 0; b < kMaxBufs; ++b) d.buf[b] = e.buf[b];
+      d.nbytes = e.nbytes;
+      d.slot = e.slot;
+      d.gen = e.gen;
+      d.nbuf = e.nbuf;
+      d.chunk_bytes = chunk_bytes_[k];
+      d.world_id = e.world_id;
+      d.world_epoch = e.world_epoch;
+      d.op_chunks = op_chunks_[k];
+      d.flags = e.flags;
+      d.target = targets_[k];
+      d.kind = kind == kCopy ? mb::kKindCopy : kind == kBcast ? mb::kKindBcast : mb::kKindReduce;
+      d.first_chunk = first_chunk_[k];
+      d.n_chunks = chunks_[k];
     }
     uint32_t first_ticket = 0;
-    int rc = mb_.submit(mb_descs_.data(), (uint32_t)n, &first_ticket);
-    // The descriptors are queued whether or not the kernel could be started (attend() tries again at the next poll).
-    for (int i = 0; i < n; ++i) {
-      const Ent& e = ents_[(size_t)i];
-      counts_[e.slot] = mb_descs_[(size_t)i].target;
-      launched_[e.group] = 1;
+    if (mb_.submit(mb_descs_.data(), (uint32_t)n, &first_ticket) != 0) {
+      (void)entries_are_on_their_way();
+      return MW_EHIP;
     }
-    ents_.clear();
-    return rc == 0 ? MW_OK : MW_EHIP;
+    return MW_OK;
   }
 
  public:
@@ -1514,6 +1516,7 @@ class HipDevice : public Device {
   hipStream_t mb_stream_ = nullptr;          // resident kernels run one after the other on it
   mb::MailboxHost<HipDevice> mb_{this};
   std::vector<mb::Desc> mb_descs_;
+  std::vector<uint32_t> first_chunk_;  // per entry: chunks of the same operation in earlier entries
   bool via_mailbox_ = false;                 // the current launch_group() call hands its entries to the mailbox
 
   int fail_inval() {
