@@ -30,8 +30,8 @@ POOL_K = 4
 # HBM bytes per mw_k_copy launch of this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (summary in
 # profiles/mw_k_copy_config2_hbm_counters.txt).  Valid only for the kernel source it was taken with: once
 # csrc/mw_device.hip changes, `traffic` is reported as null until the counters are taken again.
-PMC_TRAFFIC = {"sha256": "52fd16a968fc69842ed6085230ae1d56babd3b599dfa90f438bdbf04ea2d4fd8",
-               "bytes_per_launch": 8592004972}
+PMC_TRAFFIC = {"sha256": "e0c1f2af70839694a6a09fa4e55869bbeb1f696533942c78d91a8b6f783711dc",
+               "bytes_per_launch": 8592006220}
 
 
 def parse():
