@@ -10,6 +10,7 @@ There is no fallback: if the library is missing or fails to load, the first call
 from __future__ import annotations
 
 import ctypes as C
+import threading
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -145,8 +146,23 @@ def _ck(rc, where):
     return rc
 
 
+_NO_STREAM = C.c_void_p(-1).value  # MW_STREAM_NONE as the integer a c_void_p argument takes
+
+
 def _stream(s):
-    return C.c_void_p(s if s != STREAM_NONE else C.c_void_p(-1).value)
+    return s if s != STREAM_NONE else _NO_STREAM
+
+
+_tls = threading.local()
+
+
+def _out():
+    """This thread's handle out-parameter and a reference to it (made once: they are on every post's path)."""
+    h = getattr(_tls, "h", None)
+    if h is None:
+        h = _tls.h = C.c_uint64(0)
+        _tls.ref = C.byref(h)
+    return h, _tls.ref
 
 
 def mw_init(hip_device, n_workers):
@@ -175,52 +191,68 @@ def mw_world_state(world_id):
 
 
 def mw_send(world, src_rank, dst_rank, buf, count, dtype, stream=0):
-    h = C.c_uint64(0)
-    _ck(lib().mw_send(world, src_rank, dst_rank, buf, count, dtype, _stream(stream), C.byref(h)), "mw_send")
+    h, ref = _out()
+    rc = lib().mw_send(world, src_rank, dst_rank, buf, count, dtype, _stream(stream), ref)
+    if rc < 0:
+        raise MwError(rc, "mw_send")
     return h.value
 
 
 def mw_recv(world, src_rank, dst_rank, buf, count, dtype, stream=0):
-    h = C.c_uint64(0)
-    _ck(lib().mw_recv(world, src_rank, dst_rank, buf, count, dtype, _stream(stream), C.byref(h)), "mw_recv")
+    h, ref = _out()
+    rc = lib().mw_recv(world, src_rank, dst_rank, buf, count, dtype, _stream(stream), ref)
+    if rc < 0:
+        raise MwError(rc, "mw_recv")
     return h.value
 
 
 def mw_broadcast(world, rank, root_rank, buf, count, dtype, stream=0):
-    h = C.c_uint64(0)
-    _ck(lib().mw_broadcast(world, rank, root_rank, buf, count, dtype, _stream(stream), C.byref(h)), "mw_broadcast")
+    h, ref = _out()
+    rc = lib().mw_broadcast(world, rank, root_rank, buf, count, dtype, _stream(stream), ref)
+    if rc < 0:
+        raise MwError(rc, "mw_broadcast")
     return h.value
 
 
 def mw_allreduce_sum(world, rank, buf, count, dtype, stream=0):
-    h = C.c_uint64(0)
-    _ck(lib().mw_allreduce_sum(world, rank, buf, count, dtype, _stream(stream), C.byref(h)), "mw_allreduce_sum")
+    h, ref = _out()
+    rc = lib().mw_allreduce_sum(world, rank, buf, count, dtype, _stream(stream), ref)
+    if rc < 0:
+        raise MwError(rc, "mw_allreduce_sum")
     return h.value
 
 
 def mw_reduce_sum(world, rank, root_rank, buf, count, dtype, stream=0):
-    h = C.c_uint64(0)
-    _ck(lib().mw_reduce_sum(world, rank, root_rank, buf, count, dtype, _stream(stream), C.byref(h)), "mw_reduce_sum")
+    h, ref = _out()
+    rc = lib().mw_reduce_sum(world, rank, root_rank, buf, count, dtype, _stream(stream), ref)
+    if rc < 0:
+        raise MwError(rc, "mw_reduce_sum")
     return h.value
 
 
 def mw_all_gather(world, rank, sendbuf, recvbuf, count, dtype, stream=0):
-    h = C.c_uint64(0)
-    _ck(lib().mw_all_gather(world, rank, sendbuf, recvbuf, count, dtype, _stream(stream), C.byref(h)), "mw_all_gather")
+    h, ref = _out()
+    rc = lib().mw_all_gather(world, rank, sendbuf, recvbuf, count, dtype, _stream(stream), ref)
+    if rc < 0:
+        raise MwError(rc, "mw_all_gather")
     return h.value
 
 
 def mw_gather(world, rank, root_rank, sendbuf, recvbuf, count, dtype, stream=0):
     """recvbuf: None on every rank but the root."""
-    h = C.c_uint64(0)
-    _ck(lib().mw_gather(world, rank, root_rank, sendbuf, recvbuf, count, dtype, _stream(stream), C.byref(h)), "mw_gather")
+    h, ref = _out()
+    rc = lib().mw_gather(world, rank, root_rank, sendbuf, recvbuf, count, dtype, _stream(stream), ref)
+    if rc < 0:
+        raise MwError(rc, "mw_gather")
     return h.value
 
 
 def mw_scatter(world, rank, root_rank, sendbuf, recvbuf, count, dtype, stream=0):
     """sendbuf: None on every rank but the root."""
-    h = C.c_uint64(0)
-    _ck(lib().mw_scatter(world, rank, root_rank, sendbuf, recvbuf, count, dtype, _stream(stream), C.byref(h)), "mw_scatter")
+    h, ref = _out()
+    rc = lib().mw_scatter(world, rank, root_rank, sendbuf, recvbuf, count, dtype, _stream(stream), ref)
+    if rc < 0:
+        raise MwError(rc, "mw_scatter")
     return h.value
 
 
@@ -385,8 +417,10 @@ def mw_debug_ring_read(world_id):
 
 
 def mw_debug_arena_hash(except_world=-1):
-    h = C.c_uint64(0)
-    _ck(lib().mw_debug_arena_hash(except_world, C.byref(h)), "mw_debug_arena_hash")
+    h, ref = _out()
+    rc = lib().mw_debug_arena_hash(except_world, ref)
+    if rc < 0:
+        raise MwError(rc, "mw_debug_arena_hash")
     return h.value
 
 
