@@ -55,7 +55,7 @@ def parse():
     ap.add_argument("--mailbox", type=int, default=1, choices=[0, 1],
                     help="1 (the library's default) = small flushes go to the resident mailbox kernel, 0 = every flush is launched")
     ap.add_argument("--mailbox-workers", type=int, default=0, help="workgroups of the resident kernel (0 = the library's default)")
-    ap.add_argument("--reduce-lds", type=int, default=0, help="config3: 1 = LDS-staged all-reduce kernel")
+    ap.add_argument("--reduce-lds", type=int, default=0, help="1 = LDS-staged reduction kernel (config3, config5, collectives)")
     ap.add_argument("--c3-depth", type=int, default=3, help="config3: iterations in flight (each on input sets of its own)")
     ap.add_argument("--coll-launches", type=int, default=200, help="collectives: timed launches per operation")
     ap.add_argument("--coll-warmup", type=int, default=20, help="collectives: untimed launches per operation")
@@ -1255,6 +1255,7 @@ def main():
     torch.cuda.set_device(dev)
     mw.mw_config_set("chunk_bytes", args.chunk_bytes)
     mw.mw_config_set("mailbox", args.mailbox)
+    mw.mw_config_set("reduce_lds", args.reduce_lds)
     if args.mailbox_workers:
         mw.mw_config_set("mailbox_workers", args.mailbox_workers)
     if args.workload == "config2":
