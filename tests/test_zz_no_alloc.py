@@ -152,11 +152,22 @@ def _run_pair(torch, mw, scale, seed, stream):
     return len(pb.descs)
 
 
+def _used_stream(torch):
+    """A caller's stream that has run something already.  The runtime sets a stream's hardware queue up at the stream's
+    first launch (2 MiB of device memory on this machine): that belongs to the stream, not to what is launched on it,
+    and the free-memory check below must not see it."""
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        torch.zeros(16, device="cuda").add_(1)
+    s.synchronize()
+    return s
+
+
 def test_noalloc_entry_point_matches_post_many_on_two_calls_in_a_row(torch, mw):
     mw.mw_world_create(0, [0, 1])
     mw.mw_world_create(1, [2, 3, 4])
     mw.mw_world_create(2, [5, 6, 7, 8])
-    s = torch.cuda.Stream()
+    s = _used_stream(torch)
     assert _run_pair(torch, mw, scale=40, seed=1, stream=s) == 6 + 3 + 9 + 8 + 4  # several hundred chunks per kind
     _run_pair(torch, mw, scale=1, seed=2, stream=s)  # the second call is smaller: stale counters would show here
     _run_pair(torch, mw, scale=7, seed=3, stream=s)
@@ -191,3 +202,38 @@ def test_noalloc_entry_point_refuses_what_it_cannot_run(torch, mw):
     assert mw.mw_post_many_noalloc(ok, s.cuda_stream) == mw.MW_OK
     s.synchronize()
     assert mw.mw_poll(h) == mw.MW_PENDING and bool((buf[2048:2112] == 7).all()) and bool((buf[1024:1088] == 0).all())
+
+
+def test_noalloc_entry_point_recorded_into_a_graph_and_replayed(torch, mw):
+    """One of the callers the entry point is for: code under HIP graph capture.  The call is recorded into a graph
+    once (nothing may allocate or clear memory with a memset node there) and the graph replayed four times, with eager
+    work -- new inputs, cleared outputs, a synchronisation -- between the replays; every replay against the oracle."""
+    mw.mw_world_create(0, [0, 1])
+    mw.mw_world_create(1, [2, 3, 4, 5])
+    n, m = 70001, 4099
+    rng = np.random.default_rng(77)
+    src = torch.zeros(n, dtype=torch.int32, device="cuda")
+    dst = torch.zeros(n, dtype=torch.int32, device="cuda")
+    xs = [torch.zeros(m, dtype=torch.float32, device="cuda") for _ in range(4)]
+    posts = [(mw.POST_SEND, 0, 0, 1, src.data_ptr(), n, mw.MW_F32, 0), (mw.POST_RECV, 0, 0, 1, dst.data_ptr(), n, mw.MW_F32, 0)]
+    posts += [(mw.POST_ALLREDUCE_SUM, 1, r, 0, xs[r].data_ptr(), m, mw.MW_F32, 0) for r in range(4)]
+    pb = mw.PostBatch(posts)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        assert mw.mw_post_many_noalloc(pb, stream=s.cuda_stream) == 0
+    for k in range(4):
+        hsrc = rng.integers(-2 ** 31, 2 ** 31 - 1, size=n, dtype=np.int64).astype(np.int32)
+        hx = [rng.uniform(-1, 1, m).astype(np.float32) for _ in range(4)]
+        src.copy_(torch.from_numpy(hsrc))
+        dst.fill_(0x5A5A5A5A)
+        for x, h in zip(xs, hx):
+            x.copy_(torch.from_numpy(h))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(dst.cpu().numpy().view(np.uint8), oracle.copy_result(hsrc.view(np.uint8))), k
+        want = oracle.allreduce_sum_ordered([h.view(np.uint8) for h in hx], m, "f32")
+        for r in range(4):
+            assert np.array_equal(xs[r].cpu().numpy().view(np.uint8), want), (k, r)
