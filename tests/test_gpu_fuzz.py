@@ -6,6 +6,7 @@ agree (operations that end mismatched, broken or pending must not have touched m
 integers and are re-drawn before sums could leave the exactly representable range, so reductions compare
 bit for bit as well."""
 
+import os
 import time
 
 import numpy as np
@@ -55,7 +56,8 @@ def fresh_arena(rng):
     return arena
 
 
-@pytest.mark.parametrize("seed", range(3))
+# MW_FUZZ_SEEDS=N runs N seeded sequences instead of 3 (a longer hunt; every one must pass)
+@pytest.mark.parametrize("seed", range(int(os.environ.get("MW_FUZZ_SEEDS", "3"))))
 def test_random_sequences_with_payload_agree_with_the_oracle(torch, mw, seed):
     STATE = {mw.MW_DONE: DONE, mw.MW_PENDING: PENDING, mw.MW_BROKEN: BROKEN, mw.MW_EMISMATCH: MISMATCH}
     rng = np.random.default_rng(7000 + seed)
