@@ -128,7 +128,15 @@ struct Model {
   void ring(uint32_t t) { tail.store(t, std::memory_order_release); }
   void ask_stop(uint32_t epoch) { stop.store(epoch, std::memory_order_release); }
   uint64_t closed() { return closed_word.load(std::memory_order_acquire); }
+  // A launch can fail (the runtime may refuse it): every `fail_every`-th does, when set.  Nothing is started then; the
+  // descriptors stay queued and a later attend() must start the kernel.
+  int fail_every = 0;
+  long launch_calls = 0, failed_launches = 0;
   int launch(uint32_t epoch, uint32_t first) {
+    if (fail_every && ++launch_calls % fail_every == 0) {
+      ++failed_launches;
+      return 1;
+    }
     { std::lock_guard<std::mutex> g(mu); launches.emplace_back(epoch, first); }
     cv.notify_all();
     return 0;
@@ -142,6 +150,7 @@ int main(int argc, char** argv) {
   for (unsigned seed = 1; seed <= 3; ++seed) {
     const int W = seed == 1 ? 3 : seed == 2 ? 7 : 5;
     Model m(W, max_tickets, /*idle*/ seed == 1 ? 30e-6 : 2e-3, /*life*/ seed == 2 ? 200e-6 : 5e-3);
+    if (seed == 3) m.fail_every = 7;
     MailboxHost<Model> host(&m);
     std::mt19937 rng(seed);
     std::vector<uint32_t> chunks(max_tickets + 2, 0);
@@ -165,13 +174,14 @@ int main(int argc, char** argv) {
             batch.push_back(d);
           }
           uint32_t first = 0;
-          CHECK(host.submit(batch.data(), n, &first) == 0 && first == issued + 1);
+          const int rc = host.submit(batch.data(), n, &first);  // (a failed launch leaves the descriptors queued)
+          CHECK((rc == 0 || m.fail_every) && first == issued + 1);
           issued += n;
         }
       } else if (r < 60) {
         if (seed != 2 || rng() % 64 == 0) host.stop();  // a bulk launch is coming (rarely with seed 2: its kernels end by lifetime)
       } else if (r < 90) {  // a poll: look after orphans, see what is complete
-        if (host.needs_attention()) CHECK(host.attend() == 0);
+        if (host.needs_attention()) CHECK(host.attend() == 0 || m.fail_every);
         while (verified < issued && m.done[verified + 1].load() == chunks[verified + 1]) ++verified;
       } else {
         std::this_thread::sleep_for(std::chrono::microseconds(rng() % 120));  // long enough for the kernel to idle out
@@ -179,7 +189,7 @@ int main(int argc, char** argv) {
     }
     const double t_drain = now();
     while (verified < issued) {  // the worker polls until everything is complete
-      if (host.needs_attention()) CHECK(host.attend() == 0);
+      if (host.needs_attention()) CHECK(host.attend() == 0 || m.fail_every);
       while (verified < issued && m.done[verified + 1].load() == chunks[verified + 1]) ++verified;
       CHECK(now() - t_drain < 20.0);
     }
@@ -193,6 +203,7 @@ int main(int argc, char** argv) {
     }
     std::printf("seed %u: workers %d, tickets %u, epochs %ld (closed by idle %ld, by stop %ld, by life %ld)\n", seed, W, issued,
                 m.epochs.load(), m.closes_idle.load(), m.closes_stop.load(), m.closes_life.load());
+    if (m.fail_every) std::printf("        %ld of %ld launches refused, every descriptor served all the same\n", m.failed_launches, m.launch_calls);
     total_epochs += m.epochs.load();
     total_tickets += issued;
   }

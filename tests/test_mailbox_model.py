@@ -1,6 +1,6 @@
 """The mailbox protocol without a GPU: the library's own host side (csrc/mw_mailbox.hpp) against threads that play
 the resident kernel (tests/mailbox_model.cpp) -- kernels that close by idling out, by the host's request and by
-their lifetime while the host keeps submitting.  Every chunk of every descriptor must be executed exactly once, by the
+their lifetime while the host keeps submitting, and launches that are refused now and then.  Every chunk of every descriptor must be executed exactly once, by the
 worker that owns it, and every kernel thread must end; ThreadSanitizer must see no race in the host-side protocol."""
 
 import os
@@ -37,6 +37,9 @@ def test_every_chunk_is_executed_exactly_once_whatever_ends_the_kernels(tmp_path
     assert len(rows) == 3
     # each way a kernel can end was exercised: idling out, the host's request, the lifetime
     assert sum(r[0] for r in rows) > 0 and sum(r[1] for r in rows) > 0 and sum(r[2] for r in rows) > 0, out
+    # ... and launches of the kernel were refused now and then: the descriptors stayed queued and were served later
+    refused = [line for line in out.splitlines() if "launches refused" in line]
+    assert len(refused) == 1 and int(refused[0].split()[0]) > 0, out
 
 
 def test_the_host_side_of_the_mailbox_is_race_free(tmp_path):
