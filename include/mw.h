@@ -254,7 +254,7 @@ int mw_poll_many(const mw_handle* handles, int n, int* states);
 
 /* Tunables.  key: "chunk_bytes" (power of two, 4096..4194304; 0 = choose per launch), "reduce_lds" (0/1: stage
  * all-reduce tiles through LDS), "mailbox" (0/1, see below), "mailbox_idle_us" (10..50000, default 300) -- these four may be set at any time; "ring_depth" (1..256
- * slots per world, default 128), "max_rings", "handle_capacity", "mailbox_workers" (1..1023, default 255) -- only before
+ * slots per world, default 128), "max_rings", "handle_capacity", "mailbox_workers" (1..1023, default 255; never more than the GPU's compute units less one are used) -- only before
  * mw_init.  MW_EINVAL for unknown keys or bad values.
  *
  * "mailbox" = 1 (the default) turns on the resident mailbox kernel: a flush whose operations have final buffers (no busy caller

@@ -185,6 +185,34 @@ def test_the_idle_time_is_configurable(mailbox, torch):
         mw.mw_config_set("mailbox_idle_us", before)
 
 
+def test_more_workers_than_compute_units_are_not_used(mailbox, torch):
+    """A worker that is not resident serves its chunks only when the others have left (hundreds of microseconds later):
+    the library uses at most one workgroup per compute unit, whatever "mailbox_workers" asks for."""
+    mw = mailbox
+    before = mw.mw_config_get("mailbox_workers")
+    mw.mw_config_set("mailbox_workers", 700)
+    mw.mw_init(0, 2)
+    try:
+        mw.mw_world_create(0, [0, 1])
+        n = 70001  # five chunks: five workers per message, a different five every time
+        src = torch.randint(0, 2 ** 31 - 1, (n,), dtype=torch.int32, device="cuda")
+        dst = torch.zeros(n, dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
+        took = []
+        for k in range(300):
+            t0 = time.perf_counter()
+            hs = [mw.mw_send(0, 0, 1, src.data_ptr(), n, mw.MW_F32, mw.STREAM_NONE),
+                  mw.mw_recv(0, 0, 1, dst.data_ptr(), n, mw.MW_F32, mw.STREAM_NONE)]
+            assert _wait(mw, hs) == [mw.MW_DONE] * 2
+            took.append(time.perf_counter() - t0)
+        took.sort()
+        assert mw.mw_debug_mailbox()[2] == 300 and bool(torch.equal(src, dst))
+        assert took[len(took) // 2] < 100e-6, took[len(took) // 2]  # (with workers left out of the chip: > 300 us)
+    finally:
+        mw.mw_shutdown()
+        mw.mw_config_set("mailbox_workers", before)
+
+
 def test_more_descriptors_than_one_kernel_serves(mailbox, torch):
     """A resident kernel serves at most half the queue (2048 descriptors); 6000 one-chunk messages in windows of 16
     go through several kernels, with some windows launched the ordinary way while one kernel ends and the next has
