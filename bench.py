@@ -30,8 +30,8 @@ POOL_K = 4
 # HBM bytes per mw_k_copy launch of this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (summary in
 # profiles/mw_k_copy_config2_hbm_counters.txt).  Valid only for the kernel source it was taken with: once
 # csrc/mw_device.hip changes, `traffic` is reported as null until the counters are taken again.
-PMC_TRAFFIC = {"sha256": "e0c1f2af70839694a6a09fa4e55869bbeb1f696533942c78d91a8b6f783711dc",
-               "bytes_per_launch": 8592006220}
+PMC_TRAFFIC = {"sha256": "10dafa45a56589b320761736793a35b8fc09b5faa80766c624b836ec508d546d",
+               "bytes_per_launch": 8592007339}
 
 
 def parse():
